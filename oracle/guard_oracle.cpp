@@ -1,0 +1,252 @@
+// CPU oracle for the online straggler detector -- TEST INFRASTRUCTURE ONLY.
+//
+// This file is the plain, slow, obviously-correct statement of what the GPU
+// library must compute.  Only the tests, the smoke check and the benchmark's
+// CPU-baseline leg may call it; the product never does, and it shares no code
+// with the HIP sources.
+//
+// What it follows.  The paper (Section 4.2, "Online Monitoring Strategy")
+// fixes the shape of the decision and nothing else:
+//   * every metric is judged relative to the peers of the same job, not
+//     against absolute thresholds                       -> go_score (median,
+//                                                          MAD, robust z)
+//   * a node is flagged only when several indicators deviate, with training
+//     step time as the primary one                      -> go_score (combine)
+//   * and only when the deviation is sustained over consecutive evaluation
+//     windows                                           -> go_window
+//   * the unit acted upon is the 8-GPU node (Section 7.1) -> node scores,
+//                                                          go_flags, go_topk
+// The estimators and constants (median, MAD x 1.4826, threshold, k-of-W,
+// scaled node sum, ranking key) are this repository's stated reading of those
+// sentences; each function says which rule it implements.
+//
+// Arithmetic: IEEE fp32, round-to-nearest-even, one rounding per written
+// operation (compile with -ffp-contract=off, no fast-math), denormals kept.
+// Selection is done by sorting; windows are re-summed from scratch.
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+extern "C" {
+
+struct go_config {
+    uint32_t n_ranks;        // R, multiple of gpus_per_node
+    uint32_t gpus_per_node;  // G
+    uint32_t n_metrics;      // M in 1..8
+    uint32_t primary_metric;
+    uint32_t min_signals;
+    uint32_t window;         // W
+    uint32_t persist_k;      // k
+    uint32_t node_agg;       // 0 = scaled sum, 1 = max
+    float z_threshold;
+    float node_scale;
+    float rel_floor;
+    float abs_floor;
+    int8_t direction[8];     // +1, -1, or 0 (two-sided)
+};
+
+}  // extern "C"
+
+namespace {
+
+// Rule "order": values compare numerically; a negative zero is read as +0.
+inline float canon(float v) { return v == 0.0f ? 0.0f : v; }
+
+// Rule "median": sort; odd count -> the middle value; even count -> the two
+// middle values added, then halved, each step rounded to fp32.
+float median_by_sort(std::vector<float>& v) {
+    std::sort(v.begin(), v.end());
+    const size_t n = v.size();
+    if (n & 1) return v[n / 2];
+    float s = v[n / 2 - 1] + v[n / 2];
+    return 0.5f * s;
+}
+
+// Rule "signed score": z' = z for direction +1, -z for -1, |z| for 0.
+inline float signed_score(float z, int dir) {
+    if (dir > 0) return z;
+    if (dir < 0) return -z;
+    return std::fabs(z);
+}
+
+inline bool near_threshold(float zs, float thr) {
+    return std::fabs((double)zs - (double)thr) <= 1e-5 * std::fabs((double)thr);
+}
+
+// Order-preserving map fp32 -> u32 (larger float <=> larger integer).
+inline uint32_t order_key(float f) {
+    uint32_t b;
+    std::memcpy(&b, &f, 4);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+}  // namespace
+
+extern "C" {
+
+// The median rule on its own (any count >= 1), after reading -0 as +0.
+float go_median(const float* v, uint64_t n) {
+    std::vector<float> w(n);
+    for (uint64_t i = 0; i < n; ++i) w[i] = canon(v[i]);
+    return median_by_sort(w);
+}
+
+// Score T steps of x[t][m][r].
+//   med, mad        [T][M]
+//   z               [T][M][R] or null        (unsigned robust z, before direction)
+//   exceed_mask     [T][R]   bit m = metric m exceeds for that rank
+//   rank_anom       [T][ceil(R/64)] bit (r%64) of word r/64
+//   node_z          [T][N]   node score of the primary metric
+//   node_mask       [T][N]   bit m = node score of metric m exceeds
+//   node_anom       [T][ceil(N/64)]
+//   node_z_all      [T][M][N] or null        (node score of every metric)
+//   near            [2] or null: += number of rank / node comparisons whose score
+//                   lies within 1e-5 (relative) of the threshold
+void go_score(const go_config* c, const float* x, uint64_t T, float* med, float* mad, float* z,
+              uint8_t* exceed_mask, uint64_t* rank_anom, float* node_z, uint8_t* node_mask,
+              uint64_t* node_anom, float* node_z_all, uint64_t* near) {
+    const size_t R = c->n_ranks, G = c->gpus_per_node, M = c->n_metrics, N = R / G;
+    const size_t RW = (R + 63) / 64, NW = (N + 63) / 64;
+    const float thr = c->z_threshold;
+    uint64_t near_rank = 0, near_node = 0;
+#pragma omp parallel for schedule(dynamic, 1) reduction(+ : near_rank, near_node)
+    for (int64_t t = 0; t < (int64_t)T; ++t) {
+        std::vector<float> col(R), work(R), zs(R), nz(N);
+        std::vector<uint8_t> E(R, 0), NE(N, 0);
+        for (size_t m = 0; m < M; ++m) {
+            const float* xc = x + ((size_t)t * M + m) * R;
+            for (size_t r = 0; r < R; ++r) col[r] = canon(xc[r]);
+            // peer baseline: median over the ranks of this step and metric
+            work = col;
+            const float md = median_by_sort(work);
+            // spread: median of absolute deviations from that median
+            for (size_t r = 0; r < R; ++r) work[r] = std::fabs(col[r] - md);
+            const float ma = median_by_sort(work);
+            med[(size_t)t * M + m] = md;
+            mad[(size_t)t * M + m] = ma;
+            // scale with floors, so that a column with MAD = 0 stays finite
+            float s = 1.4826f * ma;
+            float fl = c->rel_floor * std::fabs(md);
+            s = std::max(s, fl);
+            s = std::max(s, c->abs_floor);
+            const int dir = c->direction[m];
+            for (size_t r = 0; r < R; ++r) {
+                float d = col[r] - md;
+                float zr = d / s;
+                if (z) z[((size_t)t * M + m) * R + r] = zr;
+                zs[r] = signed_score(zr, dir);
+                if (zs[r] > thr) E[r] |= (uint8_t)(1u << m);
+                if (near_threshold(zs[r], thr)) ++near_rank;
+            }
+            // node score over the node's G consecutive ranks
+            for (size_t n = 0; n < N; ++n) {
+                const float* q = &zs[n * G];
+                float v;
+                if (c->node_agg == 0) {
+                    // pairwise tree, fixed order (G == 8)
+                    float a01 = q[0] + q[1], a23 = q[2] + q[3];
+                    float a45 = q[4] + q[5], a67 = q[6] + q[7];
+                    float lo = a01 + a23, hi = a45 + a67;
+                    float sum = lo + hi;
+                    v = c->node_scale * sum;
+                } else {
+                    v = q[0];
+                    for (size_t g = 1; g < G; ++g) v = std::max(v, q[g]);
+                }
+                nz[n] = v;
+                if (v > thr) NE[n] |= (uint8_t)(1u << m);
+                if (near_threshold(v, thr)) ++near_node;
+                if (node_z_all) node_z_all[((size_t)t * M + m) * N + n] = v;
+                if (m == c->primary_metric) node_z[(size_t)t * N + n] = v;
+            }
+        }
+        // multi-signal rule: the primary metric must exceed, and at least
+        // min_signals metrics in total
+        for (size_t w = 0; w < RW; ++w) rank_anom[(size_t)t * RW + w] = 0;
+        for (size_t r = 0; r < R; ++r) {
+            exceed_mask[(size_t)t * R + r] = E[r];
+            bool a = ((E[r] >> c->primary_metric) & 1u) &&
+                     (uint32_t)__builtin_popcount(E[r]) >= c->min_signals;
+            if (a) rank_anom[(size_t)t * RW + r / 64] |= (uint64_t)1 << (r % 64);
+        }
+        for (size_t w = 0; w < NW; ++w) node_anom[(size_t)t * NW + w] = 0;
+        for (size_t n = 0; n < N; ++n) {
+            node_mask[(size_t)t * N + n] = NE[n];
+            bool a = ((NE[n] >> c->primary_metric) & 1u) &&
+                     (uint32_t)__builtin_popcount(NE[n]) >= c->min_signals;
+            if (a) node_anom[(size_t)t * NW + n / 64] |= (uint64_t)1 << (n % 64);
+        }
+    }
+    if (near) {
+        near[0] += near_rank;
+        near[1] += near_node;
+    }
+}
+
+// Persistence ("sustained over consecutive evaluation windows"): for every
+// item i (a rank or a node) and every step t of the whole history,
+//   c_i(t) = number of anomalous steps among the last W steps ending at t
+// recomputed by an explicit loop; flag_i(t) = c_i(t) >= k; first_i = first t
+// with a flag, or -1.  anom is the full history [T][ceil(n/64)] from step 0.
+//   count, flag : values at the last step (all zero if T == 0)
+//   first       : over the whole history
+//   count_hist  : [T][n] or null
+void go_window(uint32_t n, const uint64_t* anom, uint64_t T, uint32_t W, uint32_t k,
+               uint16_t* count, uint8_t* flag, int32_t* first, uint16_t* count_hist) {
+    const size_t words = ((size_t)n + 63) / 64;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < (int64_t)n; ++i) {
+        std::vector<uint8_t> a(T);
+        for (uint64_t t = 0; t < T; ++t) a[t] = (anom[t * words + i / 64] >> (i % 64)) & 1u;
+        int32_t f = -1;
+        uint32_t c = 0;
+        for (uint64_t t = 0; t < T; ++t) {
+            uint64_t lo = t + 1 >= W ? t + 1 - W : 0;
+            c = 0;
+            for (uint64_t u = lo; u <= t; ++u) c += a[u];
+            if (c >= k && f < 0) f = (int32_t)t;
+            if (count_hist) count_hist[t * n + i] = (uint16_t)c;
+        }
+        count[i] = (uint16_t)c;
+        flag[i] = (T > 0 && c >= k) ? 1 : 0;
+        first[i] = f;
+    }
+}
+
+// Node flag byte reported to the operator: bit 0 = the node's own persistence
+// flag, bit 1 = at least one of its G ranks is currently flagged.
+void go_node_flag_byte(uint32_t N, uint32_t G, const uint8_t* node_flag, const uint8_t* rank_flag,
+                       uint8_t* out) {
+    for (uint32_t n = 0; n < N; ++n) {
+        uint8_t b = node_flag[n] ? 1 : 0;
+        for (uint32_t g = 0; g < G; ++g)
+            if (rank_flag[(size_t)n * G + g]) b |= 2;
+        out[n] = b;
+    }
+}
+
+// Ranking of the slowest nodes: order all nodes by (persistence count, high
+// first; latest primary node score, high first, compared numerically; node
+// index, low first) and return the first k with the packed key
+//   count << 48 | order_key(score) << 16 | (0xFFFF - index).
+void go_topk(uint32_t N, const uint16_t* node_count, const float* node_z_last, uint32_t k,
+             int32_t* idx, uint64_t* key) {
+    std::vector<uint32_t> order(N);
+    for (uint32_t n = 0; n < N; ++n) order[n] = n;
+    std::sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
+        if (node_count[a] != node_count[b]) return node_count[a] > node_count[b];
+        float za = node_z_last[a], zb = node_z_last[b];
+        if (za != zb) return za > zb;
+        return a < b;
+    });
+    for (uint32_t j = 0; j < k && j < N; ++j) {
+        uint32_t n = order[j];
+        idx[j] = (int32_t)n;
+        key[j] = ((uint64_t)node_count[n] << 48) |
+                 ((uint64_t)order_key(canon(node_z_last[n])) << 16) | (uint64_t)(0xFFFFu - n);
+    }
+}
+
+}  // extern "C"
