@@ -1,0 +1,175 @@
+/*
+ * guard.h -- C ABI of the online straggler detector's hot path on one MI355X.
+ *
+ * The library scores a dense telemetry tensor x[step][metric][rank] (fp32, rank
+ * innermost) the way the paper's online monitor decides (Section 4.2, "Online
+ * Monitoring Strategy"; nodes of 8 GPUs, Section 7.1):
+ *
+ *   gd_score_batch    every metric is judged relative to the peers of the same
+ *                     job: per (step, metric) median and MAD over the ranks,
+ *                     robust z, exceedance, the multi-signal rule with training
+ *                     step time as the primary signal, and the 8-GPU node score;
+ *   gd_update_window  a deviation only counts when it is sustained over
+ *                     consecutive evaluations: k-of-W persistence per rank and
+ *                     per node, kept as a ring of anomaly bits in device memory;
+ *   gd_flags          the current fail-slow flags and counters;
+ *   gd_topk_nodes     the k slowest nodes, ranked for the operator.
+ *
+ * The paper states the decision in words only.  The estimators and constants
+ * used here (median / MAD x 1.4826 / threshold 3.5 / k-of-W / scaled node sum)
+ * are the defaults written into gd_config below.
+ *
+ * Conventions
+ *   - Every pointer whose name starts with d_ is DEVICE memory owned by the
+ *     caller (for instance a torch tensor).  The library never allocates, frees
+ *     or keeps device memory, apart from remembering the state pointer given to
+ *     gd_bind_state, which stays caller-owned and must outlive its use.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and is asynchronous: outputs are valid once the
+ *     caller has synchronised that stream.  No call synchronises the device.
+ *   - Arguments are validated on the host before anything is launched; a call
+ *     that returns an error has launched nothing.  No exception crosses the ABI.
+ *   - Inputs must be finite.  NaN or Inf in a column is tolerated (no fault, no
+ *     out-of-bounds access) but that column's results are unspecified.
+ *   - A handle is not thread safe.  gd_score_batch is stateless; only
+ *     gd_update_window writes the bound state; gd_flags / gd_topk_nodes read it.
+ *   - The state is position independent: a byte copy of it, together with the
+ *     number of steps consumed, is a checkpoint.
+ */
+#ifndef GUARD_H_
+#define GUARD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gd_handle_s* gd_handle; /* host object; owns no device memory */
+
+typedef enum {
+    GD_OK = 0,
+    GD_ERR_INVALID_ARG = 1,      /* NULL where a pointer is required, bad sizes          */
+    GD_ERR_BAD_CONFIG = 2,       /* gd_config fails validation                           */
+    GD_ERR_BUFFER_TOO_SMALL = 3, /* state buffer smaller than gd_state_bytes             */
+    GD_ERR_UNSUPPORTED = 4,      /* valid but not built (e.g. gpus_per_node != 8)        */
+    GD_ERR_HIP = 5               /* a HIP call failed; see gd_last_error                 */
+} gd_status;
+
+typedef enum { GD_NODE_SUM_SCALED = 0, GD_NODE_MAX = 1 } gd_node_agg;
+
+#define GD_MAX_METRICS 8
+#define GD_MAX_RANKS 65536
+#define GD_MAX_WINDOW 1024
+
+typedef struct gd_config {
+    uint32_t struct_size;    /* = sizeof(gd_config)                                      */
+    uint32_t n_ranks;        /* R: 8..65536, multiple of gpus_per_node                   */
+    uint32_t gpus_per_node;  /* G: 8 (the node size of Section 7.1)                      */
+    uint32_t n_metrics;      /* M: 1..8; metric m is bit m of every mask byte            */
+    uint32_t primary_metric; /* the metric that must exceed (step time): default 0       */
+    uint32_t min_signals;    /* metrics that must exceed together: default min(2, M)     */
+    uint32_t window;         /* W: 1..1024 evaluations                                   */
+    uint32_t persist_k;      /* k: 1..W anomalous evaluations inside the window          */
+    uint32_t topk;           /* default k of gd_topk_nodes: min(64, N)                   */
+    uint32_t node_agg;       /* gd_node_agg; default GD_NODE_SUM_SCALED                  */
+    float z_threshold;       /* default 3.5; a score exceeds when it is strictly greater */
+    float node_scale;        /* default 1/sqrt(G) = 0.35355338f; 1/G gives the mean      */
+    float rel_floor;         /* default 1e-6 : scale >= rel_floor * |median|             */
+    float abs_floor;         /* default 1e-30: scale >= abs_floor                        */
+    int8_t direction[GD_MAX_METRICS]; /* +1 higher is worse, -1 lower is worse, 0 both   */
+} gd_config;
+
+/* Fill *cfg with the defaults above for the given shape (directions all +1). */
+void gd_default_config(gd_config* cfg, uint32_t n_ranks, uint32_t n_metrics, uint32_t window,
+                       uint32_t persist_k);
+
+/* Validate *cfg and make a handle.  GD_ERR_BAD_CONFIG / GD_ERR_UNSUPPORTED on a
+ * bad or unsupported configuration (then *out is NULL and gd_last_error(NULL)
+ * describes the reason). */
+gd_status gd_create(const gd_config* cfg, gd_handle* out);
+gd_status gd_destroy(gd_handle h);
+
+/* Bytes of window state for this configuration.  The caller allocates that many
+ * bytes of device memory (256-byte aligned), fills them with zeros -- an
+ * all-zero state is a fresh, empty window -- and binds them. */
+size_t gd_state_bytes(gd_handle h);
+gd_status gd_bind_state(gd_handle h, void* d_state, size_t state_bytes);
+
+/*
+ * Score T steps (Section 4.2: peer-relative evaluation, multi-signal rule with
+ * step time primary; Section 7.1: 8-GPU nodes).  With N = R/8, RW = ceil(R/64),
+ * NW = ceil(N/64):
+ *
+ *   d_x            in   [T][M][R] f32
+ *   d_med, d_mad   out  [T][M]    f32   median over ranks; median of |x - med|
+ *   d_z            out  [T][M][R] f32   (x - med)/s, s = max(1.4826f*mad,
+ *                                       rel_floor*|med|, abs_floor); may be NULL
+ *   d_exceed_mask  out  [T][R]    u8    bit m: direction[m]*z > z_threshold
+ *   d_rank_anom    out  [T][RW]   u64   bit r%64 of word r/64: primary bit set and
+ *                                       popcount(mask) >= min_signals
+ *   d_node_z       out  [T][N]    f32   node score of the primary metric:
+ *                                       node_scale*(((z0+z1)+(z2+z3))+((z4+z5)+(z6+z7)))
+ *                                       over the node's signed scores (or their max)
+ *   d_node_mask    out  [T][N]    u8    bit m: node score of metric m > z_threshold
+ *   d_node_anom    out  [T][NW]   u64   multi-signal rule applied to d_node_mask
+ *
+ * All arithmetic is IEEE fp32, one rounding per operation, -0 read as +0.
+ * T == 0 is a valid no-op.  Every output except d_z is required.
+ */
+gd_status gd_score_batch(gd_handle h, const float* d_x, uint32_t T, float* d_med, float* d_mad,
+                         float* d_z, uint8_t* d_exceed_mask, uint64_t* d_rank_anom,
+                         float* d_node_z, uint8_t* d_node_mask, uint64_t* d_node_anom,
+                         void* stream);
+
+/*
+ * Append T evaluations to the persistence windows of the bound state (Section
+ * 4.2: "sustained ... across consecutive evaluation windows").  For every rank
+ * and node, at every appended step t = first_step_index .. first_step_index+T-1:
+ * count = anomalous steps among the last W steps ending at t; the item is
+ * flagged while count >= persist_k; the first flagged step is remembered.
+ *
+ *   d_rank_anom  in  [T][RW] u64, d_node_anom in [T][NW] u64  (from gd_score_batch)
+ *   d_node_z     in  [T][N] f32; row T-1 becomes the "latest node score" used for
+ *                ranking
+ *   first_step_index  global index of the first appended step; calls must append
+ *                consecutive steps starting from 0 on a zeroed state
+ *                (first_step_index + T <= 2^31 - 1)
+ */
+gd_status gd_update_window(gd_handle h, const uint64_t* d_rank_anom, const uint64_t* d_node_anom,
+                           const float* d_node_z, uint32_t T, uint64_t first_step_index,
+                           void* stream);
+
+/*
+ * Read the current decision out of the state.
+ *   d_rank_flag  [R] u8   1 while count >= persist_k
+ *   d_rank_count [R] u16  anomalous steps inside the current window
+ *   d_rank_first [R] i32  first step at which the rank was flagged, -1 = never
+ *   d_node_flag  [N] u8   bit 0: the node's own persistence flag;
+ *                         bit 1: at least one of its 8 ranks is flagged
+ *   d_node_count [N] u16, d_node_first [N] i32: as for ranks
+ * Any of the six pointers may be NULL to skip that output.
+ */
+gd_status gd_flags(gd_handle h, uint8_t* d_rank_flag, uint16_t* d_rank_count,
+                   int32_t* d_rank_first, uint8_t* d_node_flag, uint16_t* d_node_count,
+                   int32_t* d_node_first, void* stream);
+
+/*
+ * The k slowest nodes: all N nodes ordered by (window count, high first; latest
+ * primary node score, high first, -0 == +0; node index, low first).
+ *   d_idx [k] i32  node indices in that order
+ *   d_key [k] u64  count << 48 | order_key(score) << 16 | (0xFFFF - index), where
+ *                  order_key maps fp32 to u32 preserving order; may be NULL
+ * k == 0 selects the configured default; k > N is GD_ERR_INVALID_ARG.
+ */
+gd_status gd_topk_nodes(gd_handle h, uint32_t k, int32_t* d_idx, uint64_t* d_key, void* stream);
+
+/* Text of the last error on this handle (or of the last failed gd_create when
+ * h is NULL).  The pointer stays valid until the next call on the handle. */
+const char* gd_last_error(gd_handle h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GUARD_H_ */

@@ -1,0 +1,227 @@
+// Host side of the C ABI declared in guard.h: configuration checks, the layout
+// of the caller's state buffer, argument validation and the kernel launches.
+// No device memory is allocated here and no call synchronises.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <string>
+
+#include "../../include/guard.h"
+#include "gd_internal.h"
+
+struct gd_handle_s {
+    gd_config cfg;
+    uint32_t N, RW, NW;
+    gd_state_layout lay;
+    uint8_t* d_state;
+    std::string err;
+};
+
+namespace {
+
+std::string g_create_error;
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+gd_state_layout make_layout(uint32_t R, uint32_t N, uint32_t W) {
+    const size_t RW = (R + 63) / 64, NW = (N + 63) / 64;
+    gd_state_layout l;
+    size_t o = 0;
+    l.rank_ring = o;   o = align256(o + (size_t)W * RW * 8);
+    l.node_ring = o;   o = align256(o + (size_t)W * NW * 8);
+    l.rank_count = o;  o = align256(o + (size_t)R * 2);
+    l.node_count = o;  o = align256(o + (size_t)N * 2);
+    l.rank_first = o;  o = align256(o + (size_t)R * 4);
+    l.node_first = o;  o = align256(o + (size_t)N * 4);
+    l.node_z_last = o; o = align256(o + (size_t)N * 4);
+    l.total = o;
+    return l;
+}
+
+gd_status fail(gd_handle h, gd_status st, const std::string& msg) {
+    if (h) h->err = msg; else g_create_error = msg;
+    return st;
+}
+
+gd_status hip_fail(gd_handle h, hipError_t e, const char* what) {
+    return fail(h, GD_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+}  // namespace
+
+extern "C" {
+
+void gd_default_config(gd_config* c, uint32_t n_ranks, uint32_t n_metrics, uint32_t window,
+                       uint32_t persist_k) {
+    if (!c) return;
+    memset(c, 0, sizeof(*c));
+    c->struct_size = (uint32_t)sizeof(gd_config);
+    c->n_ranks = n_ranks;
+    c->gpus_per_node = 8;
+    c->n_metrics = n_metrics;
+    c->primary_metric = 0;
+    c->min_signals = n_metrics < 2 ? n_metrics : 2;
+    c->window = window;
+    c->persist_k = persist_k;
+    const uint32_t N = n_ranks / 8;
+    c->topk = N < 64 ? N : 64;
+    c->node_agg = GD_NODE_SUM_SCALED;
+    c->z_threshold = 3.5f;
+    c->node_scale = 0.35355338f;   // 1/sqrt(8)
+    c->rel_floor = 1e-6f;
+    c->abs_floor = 1e-30f;
+    for (int i = 0; i < GD_MAX_METRICS; ++i) c->direction[i] = 1;
+}
+
+gd_status gd_create(const gd_config* c, gd_handle* out) {
+    if (out) *out = nullptr;
+    if (!c || !out) return fail(nullptr, GD_ERR_INVALID_ARG, "gd_create: null argument");
+    if (c->struct_size != sizeof(gd_config))
+        return fail(nullptr, GD_ERR_BAD_CONFIG, "struct_size does not match this library's gd_config");
+    if (c->gpus_per_node != 8)
+        return fail(nullptr, GD_ERR_UNSUPPORTED, "only gpus_per_node = 8 is built");
+    if (c->n_ranks < 8 || c->n_ranks % 8 != 0)
+        return fail(nullptr, GD_ERR_BAD_CONFIG, "n_ranks must be a positive multiple of gpus_per_node");
+    if (c->n_ranks > GD_MAX_RANKS)
+        return fail(nullptr, GD_ERR_UNSUPPORTED, "n_ranks above 65536 is not built");
+    if (c->n_metrics < 1 || c->n_metrics > GD_MAX_METRICS)
+        return fail(nullptr, GD_ERR_BAD_CONFIG, "n_metrics must be 1..8");
+    if (c->primary_metric >= c->n_metrics)
+        return fail(nullptr, GD_ERR_BAD_CONFIG, "primary_metric out of range");
+    if (c->min_signals < 1 || c->min_signals > c->n_metrics)
+        return fail(nullptr, GD_ERR_BAD_CONFIG, "min_signals must be 1..n_metrics");
+    if (c->window < 1 || c->window > GD_MAX_WINDOW)
+        return fail(nullptr, GD_ERR_BAD_CONFIG, "window must be 1..1024");
+    if (c->persist_k < 1 || c->persist_k > c->window)
+        return fail(nullptr, GD_ERR_BAD_CONFIG, "persist_k must be 1..window");
+    const uint32_t N = c->n_ranks / 8;
+    if (c->topk > N) return fail(nullptr, GD_ERR_BAD_CONFIG, "topk exceeds the number of nodes");
+    if (c->node_agg != GD_NODE_SUM_SCALED && c->node_agg != GD_NODE_MAX)
+        return fail(nullptr, GD_ERR_BAD_CONFIG, "unknown node_agg");
+    if (!isfinite(c->z_threshold) || !isfinite(c->node_scale) || !(c->rel_floor >= 0.0f) ||
+        !(c->abs_floor > 0.0f) || !isfinite(c->rel_floor) || !isfinite(c->abs_floor))
+        return fail(nullptr, GD_ERR_BAD_CONFIG,
+                    "threshold and node_scale must be finite, rel_floor >= 0, abs_floor > 0");
+    for (uint32_t m = 0; m < c->n_metrics; ++m)
+        if (c->direction[m] < -1 || c->direction[m] > 1)
+            return fail(nullptr, GD_ERR_BAD_CONFIG, "direction must be -1, 0 or +1");
+    gd_handle h = new (std::nothrow) gd_handle_s();
+    if (!h) return fail(nullptr, GD_ERR_INVALID_ARG, "out of host memory");
+    h->cfg = *c;
+    h->N = N;
+    h->RW = (c->n_ranks + 63) / 64;
+    h->NW = (N + 63) / 64;
+    h->lay = make_layout(c->n_ranks, N, c->window);
+    h->d_state = nullptr;
+    *out = h;
+    return GD_OK;
+}
+
+gd_status gd_destroy(gd_handle h) {
+    delete h;
+    return GD_OK;
+}
+
+size_t gd_state_bytes(gd_handle h) { return h ? h->lay.total : 0; }
+
+gd_status gd_bind_state(gd_handle h, void* d_state, size_t state_bytes) {
+    if (!h) return GD_ERR_INVALID_ARG;
+    if (!d_state) return fail(h, GD_ERR_INVALID_ARG, "gd_bind_state: null state");
+    if (((uintptr_t)d_state & 255) != 0)
+        return fail(h, GD_ERR_INVALID_ARG, "gd_bind_state: state must be 256-byte aligned");
+    if (state_bytes < h->lay.total)
+        return fail(h, GD_ERR_BUFFER_TOO_SMALL, "gd_bind_state: buffer smaller than gd_state_bytes");
+    h->d_state = static_cast<uint8_t*>(d_state);
+    return GD_OK;
+}
+
+gd_status gd_score_batch(gd_handle h, const float* d_x, uint32_t T, float* d_med, float* d_mad,
+                         float* d_z, uint8_t* d_exceed_mask, uint64_t* d_rank_anom,
+                         float* d_node_z, uint8_t* d_node_mask, uint64_t* d_node_anom,
+                         void* stream) {
+    if (!h) return GD_ERR_INVALID_ARG;
+    if (T == 0) return GD_OK;
+    if (!d_x || !d_med || !d_mad || !d_exceed_mask || !d_rank_anom || !d_node_z || !d_node_mask ||
+        !d_node_anom)
+        return fail(h, GD_ERR_INVALID_ARG, "gd_score_batch: a required pointer is null");
+    if (((uintptr_t)d_x & 15) || ((uintptr_t)d_z & 15) || ((uintptr_t)d_exceed_mask & 3) ||
+        ((uintptr_t)d_rank_anom & 7) || ((uintptr_t)d_node_anom & 7) || ((uintptr_t)d_node_z & 3) ||
+        ((uintptr_t)d_med & 3) || ((uintptr_t)d_mad & 3))
+        return fail(h, GD_ERR_INVALID_ARG,
+                    "gd_score_batch: x and z must be 16-byte aligned, the other arrays naturally aligned");
+    gd_score_args a;
+    a.x = d_x; a.med = d_med; a.mad = d_mad; a.z = d_z;
+    a.exceed_mask = d_exceed_mask; a.rank_anom = d_rank_anom;
+    a.node_z = d_node_z; a.node_mask = d_node_mask; a.node_anom = d_node_anom;
+    a.T = T; a.R = h->cfg.n_ranks; a.M = h->cfg.n_metrics; a.N = h->N;
+    a.primary = h->cfg.primary_metric; a.min_signals = h->cfg.min_signals;
+    a.node_agg = h->cfg.node_agg;
+    a.thr = h->cfg.z_threshold; a.node_scale = h->cfg.node_scale;
+    a.rel_floor = h->cfg.rel_floor; a.abs_floor = h->cfg.abs_floor;
+    memcpy(a.dir, h->cfg.direction, 8);
+    hipError_t e = gd_launch_score(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(h, e, "gd_score_batch");
+    return GD_OK;
+}
+
+gd_status gd_update_window(gd_handle h, const uint64_t* d_rank_anom, const uint64_t* d_node_anom,
+                           const float* d_node_z, uint32_t T, uint64_t first_step_index,
+                           void* stream) {
+    if (!h) return GD_ERR_INVALID_ARG;
+    if (!h->d_state) return fail(h, GD_ERR_INVALID_ARG, "gd_update_window: no state bound");
+    if (T == 0) return GD_OK;
+    if (!d_rank_anom || !d_node_anom || !d_node_z)
+        return fail(h, GD_ERR_INVALID_ARG, "gd_update_window: a required pointer is null");
+    if (((uintptr_t)d_rank_anom & 7) || ((uintptr_t)d_node_anom & 7) || ((uintptr_t)d_node_z & 3))
+        return fail(h, GD_ERR_INVALID_ARG, "gd_update_window: misaligned pointer");
+    if (first_step_index + (uint64_t)T > 0x7FFFFFFFull)
+        return fail(h, GD_ERR_INVALID_ARG, "gd_update_window: step index beyond 2^31 - 1");
+    gd_window_args a;
+    a.state = h->d_state; a.lay = h->lay;
+    a.rank_anom = d_rank_anom; a.node_anom = d_node_anom; a.node_z = d_node_z;
+    a.T = T; a.R = h->cfg.n_ranks; a.N = h->N; a.W = h->cfg.window; a.K = h->cfg.persist_k;
+    a.first_step = first_step_index;
+    hipError_t e = gd_launch_window(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(h, e, "gd_update_window");
+    return GD_OK;
+}
+
+gd_status gd_flags(gd_handle h, uint8_t* d_rank_flag, uint16_t* d_rank_count,
+                   int32_t* d_rank_first, uint8_t* d_node_flag, uint16_t* d_node_count,
+                   int32_t* d_node_first, void* stream) {
+    if (!h) return GD_ERR_INVALID_ARG;
+    if (!h->d_state) return fail(h, GD_ERR_INVALID_ARG, "gd_flags: no state bound");
+    if (((uintptr_t)d_rank_count & 1) || ((uintptr_t)d_node_count & 1) ||
+        ((uintptr_t)d_rank_first & 3) || ((uintptr_t)d_node_first & 3))
+        return fail(h, GD_ERR_INVALID_ARG, "gd_flags: misaligned pointer");
+    gd_flags_args a;
+    a.state = h->d_state; a.lay = h->lay;
+    a.rank_flag = d_rank_flag; a.rank_count = d_rank_count; a.rank_first = d_rank_first;
+    a.node_flag = d_node_flag; a.node_count = d_node_count; a.node_first = d_node_first;
+    a.R = h->cfg.n_ranks; a.N = h->N; a.K = h->cfg.persist_k;
+    hipError_t e = gd_launch_flags(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(h, e, "gd_flags");
+    return GD_OK;
+}
+
+gd_status gd_topk_nodes(gd_handle h, uint32_t k, int32_t* d_idx, uint64_t* d_key, void* stream) {
+    if (!h) return GD_ERR_INVALID_ARG;
+    if (!h->d_state) return fail(h, GD_ERR_INVALID_ARG, "gd_topk_nodes: no state bound");
+    if (k == 0) k = h->cfg.topk;
+    if (k == 0) return GD_OK;
+    if (k > h->N) return fail(h, GD_ERR_INVALID_ARG, "gd_topk_nodes: k exceeds the number of nodes");
+    if (!d_idx) return fail(h, GD_ERR_INVALID_ARG, "gd_topk_nodes: null index output");
+    if (((uintptr_t)d_idx & 3) || ((uintptr_t)d_key & 7))
+        return fail(h, GD_ERR_INVALID_ARG, "gd_topk_nodes: misaligned pointer");
+    gd_topk_args a;
+    a.state = h->d_state; a.lay = h->lay; a.idx = d_idx; a.key = d_key; a.N = h->N; a.k = k;
+    hipError_t e = gd_launch_topk(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(h, e, "gd_topk_nodes");
+    return GD_OK;
+}
+
+const char* gd_last_error(gd_handle h) { return h ? h->err.c_str() : g_create_error.c_str(); }
+
+}  // extern "C"

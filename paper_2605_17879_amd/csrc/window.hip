@@ -1,0 +1,129 @@
+// Sliding-window persistence (k anomalous evaluations among the last W:
+// "sustained deviation ... across consecutive evaluation windows", Section 4.2)
+// and the read-out of the current flags.
+//
+// State in HBM, per item (a rank or a node): a ring of the last W anomaly bits,
+// stored as the scoring kernel's own bit words ring[step % W][item / 64]; a u16
+// count of set bits inside the window; the first flagged step (+1, 0 = never).
+//
+// One thread owns one item and one wave owns one 64-item word column of the
+// ring, so every ring word is read and written by a single wave.  A wave loads
+// 64 steps' words at a time (lane l takes step s0 + l) and walks them through
+// lane broadcasts; the bit leaving the window at step t is the bit that entered
+// at t - W, taken from the batch itself when it is recent enough, else from the
+// ring.
+#include "gd_internal.h"
+
+namespace {
+
+constexpr int WAVE = 64;
+constexpr int WIN_NT = 256;
+
+// Value of lane l (uniform over the wave) of a 64-bit register.
+__device__ __forceinline__ uint64_t bcast64(uint64_t v, uint32_t l) {
+    const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)v, (int)l);
+    const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), (int)l);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// Items [0, R) are ranks, then, starting at a fresh workgroup, items [0, N) are nodes.
+__global__ __launch_bounds__(WIN_NT) void window_kernel(const gd_window_args a) {
+    const uint32_t rank_blocks = (a.R + WIN_NT - 1) / WIN_NT;
+    const bool is_node = blockIdx.x >= rank_blocks;
+    const uint32_t n_items = is_node ? a.N : a.R;
+    const uint32_t blk = is_node ? blockIdx.x - rank_blocks : blockIdx.x;
+    const uint32_t item = blk * WIN_NT + threadIdx.x;
+    const int lane = threadIdx.x & (WAVE - 1);
+    const uint32_t words = (n_items + 63) / 64;
+    const uint32_t word = item / 64;                 // uniform over the wave
+    if (word >= words) return;                       // whole wave out of range
+    const uint64_t* anom = is_node ? a.node_anom : a.rank_anom;
+    uint64_t* ring = reinterpret_cast<uint64_t*>(a.state + (is_node ? a.lay.node_ring : a.lay.rank_ring));
+    uint16_t* count = reinterpret_cast<uint16_t*>(a.state + (is_node ? a.lay.node_count : a.lay.rank_count));
+    int32_t* first = reinterpret_cast<int32_t*>(a.state + (is_node ? a.lay.node_first : a.lay.rank_first));
+    const bool live = item < n_items;
+    const uint32_t W = a.W, K = a.K, T = a.T;
+
+    uint32_t c = live ? count[item] : 0;
+    int32_t f = live ? first[item] : 0;
+    for (uint32_t s0 = 0; s0 < T; s0 += WAVE) {
+        // lane l fetches the entering and the leaving word of step s0 + l
+        const uint32_t s = s0 + lane;
+        uint64_t win = 0, wout = 0;
+        if (s < T) {
+            win = anom[(size_t)s * words + word];
+            const uint64_t t = a.first_step + s;
+            if (t >= W) {
+                wout = s >= W ? anom[(size_t)(s - W) * words + word]
+                              : ring[(size_t)(t % W) * words + word];
+            }
+        }
+        const uint32_t cnt = min((uint32_t)WAVE, T - s0);
+        for (uint32_t l = 0; l < cnt; ++l) {
+            const uint64_t wi = bcast64(win, l), wo = bcast64(wout, l);
+            c += (uint32_t)((wi >> lane) & 1u) - (uint32_t)((wo >> lane) & 1u);
+            if (c >= K && f == 0) f = (int32_t)(a.first_step + s0 + l) + 1;
+        }
+    }
+    if (live) {
+        count[item] = (uint16_t)c;
+        first[item] = f;
+    }
+    // The last min(T, W) words of the batch become the ring's newest slots.
+    // Every ring read above has been consumed before these stores are issued,
+    // and no other wave touches this word column.
+    const uint32_t keep = T < W ? T : W;
+    for (uint32_t i = lane; i < keep; i += WAVE) {
+        const uint32_t s = T - keep + i;
+        ring[(size_t)((a.first_step + s) % W) * words + word] = anom[(size_t)s * words + word];
+    }
+    if (is_node && live && T > 0) {
+        float* last = reinterpret_cast<float*>(a.state + a.lay.node_z_last);
+        last[item] = a.node_z[(size_t)(T - 1) * a.N + item];
+    }
+}
+
+__global__ __launch_bounds__(WIN_NT) void flags_kernel(const gd_flags_args a) {
+    const uint32_t i = blockIdx.x * WIN_NT + threadIdx.x;
+    const uint16_t* rc = reinterpret_cast<const uint16_t*>(a.state + a.lay.rank_count);
+    const int32_t* rf = reinterpret_cast<const int32_t*>(a.state + a.lay.rank_first);
+    const uint16_t* nc = reinterpret_cast<const uint16_t*>(a.state + a.lay.node_count);
+    const int32_t* nf = reinterpret_cast<const int32_t*>(a.state + a.lay.node_first);
+    if (i < a.R) {
+        const uint32_t c = rc[i];
+        if (a.rank_flag) a.rank_flag[i] = c >= a.K ? 1 : 0;
+        if (a.rank_count) a.rank_count[i] = (uint16_t)c;
+        if (a.rank_first) a.rank_first[i] = rf[i] - 1;
+    }
+    if (i < a.N) {
+        const uint32_t c = nc[i];
+        if (a.node_flag) {
+            uint8_t b = c >= a.K ? 1 : 0;
+            // 8 GPUs per node: two 8-byte loads of the ranks' counts
+            const uint4 q = *reinterpret_cast<const uint4*>(rc + (size_t)i * 8);
+            const uint32_t v[4] = {q.x, q.y, q.z, q.w};
+            bool any = false;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) any |= (v[j] & 0xFFFFu) >= a.K || (v[j] >> 16) >= a.K;
+            if (any) b |= 2;
+            a.node_flag[i] = b;
+        }
+        if (a.node_count) a.node_count[i] = (uint16_t)c;
+        if (a.node_first) a.node_first[i] = nf[i] - 1;
+    }
+}
+
+}  // namespace
+
+hipError_t gd_launch_window(const gd_window_args& a, hipStream_t s) {
+    if (a.T == 0) return hipSuccess;
+    const uint32_t blocks = (a.R + WIN_NT - 1) / WIN_NT + (a.N + WIN_NT - 1) / WIN_NT;
+    hipLaunchKernelGGL(window_kernel, dim3(blocks), dim3(WIN_NT), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t gd_launch_flags(const gd_flags_args& a, hipStream_t s) {
+    const uint32_t blocks = (a.R + WIN_NT - 1) / WIN_NT;
+    hipLaunchKernelGGL(flags_kernel, dim3(blocks), dim3(WIN_NT), 0, s, a);
+    return hipGetLastError();
+}

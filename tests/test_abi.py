@@ -1,0 +1,85 @@
+"""The C-ABI library loads and exports what include/guard.h declares; host-side
+validation answers with status codes (no kernel is launched here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2605_17879_amd import guard
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "guard.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gd_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = guard.load_library()
+    names = declared_symbols()
+    assert set(names) == set(guard.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def make(**kw):
+    lib = guard.load_library()
+    c = guard.Config(n_ranks=kw.pop("R", 64), n_metrics=kw.pop("M", 2), window=kw.pop("W", 8),
+                     persist_k=kw.pop("k", 4), **kw).to_c()
+    h = ctypes.c_void_p()
+    st = lib.gd_create(ctypes.byref(c), ctypes.byref(h))
+    return lib, st, h
+
+
+def test_defaults():
+    c = guard.Config(65536, 8, 256, 200).to_c()
+    assert c.struct_size == ctypes.sizeof(guard._CConfig) == 64
+    assert (c.gpus_per_node, c.primary_metric, c.min_signals, c.topk) == (8, 0, 2, 64)
+    assert c.z_threshold == 3.5 and abs(c.node_scale - 8 ** -0.5) < 1e-7
+    assert guard.Config(64, 1, 20, 15).to_c().min_signals == 1
+    assert guard.Config(64, 1, 20, 15).to_c().topk == 8
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(R=60), 2), (dict(R=0), 2), (dict(R=65544), 4), (dict(M=0), 2), (dict(M=9), 2),
+    (dict(W=0), 2), (dict(W=1025), 2), (dict(k=9), 2), (dict(k=0), 2), (dict(primary_metric=2), 2),
+    (dict(min_signals=3), 2), (dict(gpus_per_node=4), 4), (dict(topk=9), 2), (dict(node_agg=2), 2),
+    (dict(abs_floor=0.0), 2), (dict(z_threshold=float("nan")), 2), (dict(direction=(2, 1)), 2),
+])
+def test_bad_configurations_are_refused(kw, status):
+    lib, st, h = make(**kw)
+    assert st == status and not h.value
+    assert len(lib.gd_last_error(None)) > 0
+
+
+def test_state_size_and_argument_checks_without_a_device():
+    lib, st, h = make(R=1024, M=4, W=50, k=40)
+    assert st == 0 and h.value
+    n = lib.gd_state_bytes(h)
+    # rings + counters + first-flag steps + latest node score, each 256-byte aligned
+    want = 0
+    for b in (50 * 16 * 8, 50 * 2 * 8, 1024 * 2, 128 * 2, 1024 * 4, 128 * 4, 128 * 4):
+        want += (b + 255) // 256 * 256
+    assert n == want
+    # nothing bound yet / null pointers / misaligned: status codes, no launch
+    assert lib.gd_update_window(h, 256, 256, 256, 1, 0, None) == 1
+    assert lib.gd_flags(h, None, None, None, None, None, None, None) == 1
+    assert lib.gd_topk_nodes(h, 4, 256, None, None) == 1
+    assert lib.gd_bind_state(h, None, n) == 1
+    assert lib.gd_bind_state(h, 4096 + 8, n) == 1          # misaligned
+    assert lib.gd_bind_state(h, 4096, n - 1) == 3          # too small
+    assert lib.gd_score_batch(h, None, 1, *([256] * 8), None) == 1
+    assert lib.gd_score_batch(h, 256 + 4, 1, *([256] * 8), None) == 1   # x not 16-byte aligned
+    assert lib.gd_score_batch(h, None, 0, *([None] * 8), None) == 0     # T == 0: no-op
+    assert b"null" in lib.gd_last_error(h) or b"align" in lib.gd_last_error(h)
+    assert lib.gd_destroy(h) == 0
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(guard, "_lib", None)
+    monkeypatch.setattr(guard, "_LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        guard.load_library()

@@ -1,0 +1,179 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle on the same
+seeded inputs.  Each test prints the case it is about to run before any launch."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_harness import (compare_decision, compare_scores, detector_for, gpu_score, oracle_params,
+                         run_and_compare)
+from workloads import adversarial, generate, workload
+from workloads.telemetry import ADVERSARIAL_KINDS
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+# Rank counts spanning every register tiling of the scoring kernel, full and ragged.
+SHAPES = [(8, 1), (24, 3), (64, 1), (72, 2), (256, 4), (1000, 2), (1024, 4), (2056, 8), (4096, 3),
+          (5000, 2), (16384, 4), (20000, 2), (32768, 8), (40000, 1), (65536, 8)]
+
+
+@pytest.mark.parametrize("R,M", SHAPES)
+def test_shapes_full_and_ragged(R, M):
+    T = 5 if R <= 16384 else 3
+    say(f"case shapes R={R} M={M} T={T}")
+    g = torch.Generator().manual_seed(R * 31 + M)
+    x = torch.exp(0.02 * torch.randn((T, M, R), generator=g, dtype=torch.float64))
+    x[:, :, (R // 8 // 2) * 8: (R // 8 // 2) * 8 + 8] *= 1.07       # one slow node
+    x[:, :, 3] *= 1.2                                               # one slow GPU
+    x[:, 1::2] = 400.0 / x[:, 1::2]                                  # lower-is-worse metrics
+    x = x.to(torch.float32)
+    dirs = tuple(1 if m % 2 == 0 else -1 for m in range(M))
+    p = oracle_params(R=R, M=M, W=4, k=2, directions=dirs)
+    rep = run_and_compare(p, x, topk_k=min(8, R // 8), chunks=[2, T - 2], label=f"R{R}M{M}")
+    say("  report", rep)
+    assert rep["z_bit_exact"]
+
+
+@pytest.mark.parametrize("kind", ADVERSARIAL_KINDS)
+@pytest.mark.parametrize("R", [64, 4096, 65536])
+def test_adversarial_columns(kind, R):
+    T, M = (4, 2) if R < 65536 else (2, 2)
+    say(f"case adversarial kind={kind} R={R}")
+    x = adversarial(kind, R, T, M, seed=R % 97)
+    p = oracle_params(R=R, M=M, W=3, k=2, directions=(1, 0), min_signals=1)
+    rep = run_and_compare(p, x, topk_k=min(8, R // 8), label=f"{kind}-R{R}")
+    say("  report", rep)
+    assert rep["z_bit_exact"]
+
+
+@pytest.mark.parametrize("agg", [oracle.NODE_SUM_SCALED, oracle.NODE_MAX])
+@pytest.mark.parametrize("R", [1024, 16384])
+def test_node_aggregation_rules_and_options(agg, R):
+    say(f"case node_agg={agg} R={R}")
+    g = torch.Generator().manual_seed(5)
+    x = torch.exp(0.02 * torch.randn((6, 3, R), generator=g, dtype=torch.float64)).to(torch.float32)
+    x[2:, :, 64:72] *= 1.06
+    p = oracle_params(R=R, M=3, W=5, k=3, node_agg=agg, primary=1, min_signals=3, thr=2.5,
+                      node_scale=0.125, rel_floor=1e-3, abs_floor=1e-20, directions=(1, 0, 1))
+    rep = run_and_compare(p, x, topk_k=16, chunks=[1, 1, 4], label=f"agg{agg}")
+    say("  report", rep)
+
+
+def test_tiny_configuration():
+    w = workload(0)
+    say("case", w.name)
+    x = generate(w, seed=0)
+    rep = run_and_compare(oracle_params(w), x, topk_k=w.topk, chunks=[1] * 10 + [40, 150], label=w.name)
+    say("  report", rep)
+    assert rep["rank_flags"] == 2
+
+
+def test_configuration_1_full():
+    w = workload(1)
+    say("case", w.name)
+    x = generate(w, seed=1)
+    rep = run_and_compare(oracle_params(w), x, topk_k=w.topk, chunks=[700, 1, 1299], label=w.name,
+                          want_z=True)
+    say("  report", rep)
+    assert rep["node_flags"] >= 6      # 8 grey nodes slowed 5-30%; the mildest may stay under
+
+
+def test_configuration_2_prefix():
+    w = workload(2, T=320)
+    say("case", w.name, "first 320 steps")
+    x = generate(w, seed=2)
+    rep = run_and_compare(oracle_params(w), x, topk_k=w.topk, chunks=[120, 200], label=w.name,
+                          want_z=False)
+    say("  report", rep)
+
+
+def test_configuration_3_prefix_with_window_wrap():
+    w = workload(3, T=40, W=16, k=12, fault_ramp=8)
+    say("case", w.name, "40 steps, window shortened to 16")
+    x = generate(w, seed=3)
+    rep = run_and_compare(oracle_params(w), x, topk_k=w.topk, chunks=[24, 16], label=w.name,
+                          want_z=False)
+    say("  report", rep)
+
+
+def test_streaming_configuration_prefix():
+    """Config 4's launch shape: one step per call, ring kept on the device."""
+    w = workload(4, T=300, W=64, k=48)
+    say("case", w.name, "300 single-step calls, W=64")
+    x = generate(w, seed=4)
+    # make a few nodes fail-slow early so that flags appear inside the prefix
+    x[40:, :, 800:808] *= torch.tensor([1.2, 1.2, 1.2, 1 / 1.2, 1.2, 1 / 1.2, 1 / 1.2, 1 / 1.2])[:, None]
+    rep = run_and_compare(oracle_params(w), x, topk_k=w.topk, chunks=[1] * 300, label=w.name,
+                          want_z=False)
+    say("  report", rep)
+    assert rep["node_flags"] >= 1
+
+
+def test_checkpoint_restore_and_chunking_give_identical_state():
+    w = workload(1, T=260)
+    say("case checkpoint/chunking", w.name)
+    x = generate(w, seed=7)
+    p = oracle_params(w)
+    states = []
+    for chunks in ([260], [1] * 60 + [200], [130, 130]):
+        det = detector_for(p)
+        t0 = 0
+        for c in chunks:
+            g = gpu_score(det, x[t0:t0 + c], want_z=False)
+            det.update_window(g, c)
+            t0 += c
+        torch.cuda.synchronize()
+        states.append(det.state.cpu().numpy().copy())
+        det.close()
+    assert np.array_equal(states[0], states[1]) and np.array_equal(states[0], states[2])
+    # checkpoint = byte copy of the state + steps consumed
+    det = detector_for(p)
+    g = gpu_score(det, x[:100], want_z=False)
+    det.update_window(g, 100)
+    torch.cuda.synchronize()
+    snap = det.state.clone()
+    det.close()
+    det2 = detector_for(p)
+    det2.state.copy_(snap)
+    g = gpu_score(det2, x[100:], want_z=False)
+    det2.update_window(g, 160, first_step_index=100)
+    torch.cuda.synchronize()
+    assert np.array_equal(det2.state.cpu().numpy(), states[0])
+    d = oracle.detect(p, x.numpy(), topk_k=w.topk)
+    compare_decision(p, d, det2, w.topk, label="restored")
+    det2.close()
+
+
+def test_runs_are_deterministic():
+    w = workload(3, T=6)
+    say("case determinism", w.name)
+    x = generate(w, seed=9).cuda()
+    p = oracle_params(w)
+    det = detector_for(p)
+    a = gpu_score(det, x, want_z=True)
+    b = gpu_score(det, x, want_z=True)
+    for k in a:
+        assert torch.equal(a[k], b[k]), k
+    det.close()
+
+
+def test_device_division_is_correctly_rounded():
+    """The z scores rely on IEEE fp32 division on the device: one column whose
+    numerators and scale span many magnitudes, against the oracle's host division."""
+    say("case division rounding")
+    R = 65536
+    g = torch.Generator().manual_seed(11)
+    e = torch.rand((4, 1, R), generator=g, dtype=torch.float64) * 40 - 20
+    x = (torch.randn((4, 1, R), generator=g, dtype=torch.float64) * torch.pow(2.0, e)).to(torch.float32)
+    p = oracle_params(R=R, M=1, W=2, k=1, min_signals=1)
+    det = detector_for(p)
+    gpu = gpu_score(det, x, want_z=True)
+    o = oracle.score(p, x.numpy(), want_z=True)
+    rep = compare_scores(o, gpu, "division")
+    assert rep["z_bit_exact"]
+    det.close()
