@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Benchmark of the detector's hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic
+telemetry resident in HBM: gd_score_batch over all T steps of the workload,
+gd_update_window, gd_flags and gd_topk_nodes.  The workload is the 65 536-rank
+configuration (65 536 ranks x 4 096 steps x 8 metrics fp32, 8 GiB).
+
+Prints one JSON line: telemetry samples scored per second, the scoring
+kernel's achieved HBM bandwidth against the 8 TB/s peak (algorithmic bytes /
+HIP-event time per launch), the CPU oracle timed on a bounded sample of the
+same workload, and the streaming per-step latency on the 32 768-rank shape.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes_per_launch(R: int, M: int, T: int) -> int:
+    """What one gd_score_batch call must move: every fp32 sample read once, plus
+    per step: med+mad, mask bytes, rank bits, primary node score, node mask, node bits."""
+    N = R // 8
+    per_step = 4 * M * R + 8 * M + R + R // 8 + 4 * N + N + N // 8
+    return per_step * T
+
+
+def make_detector(w):
+    from paper_2605_17879_amd import Config, Detector
+    return Detector(Config(n_ranks=w.R, n_metrics=w.M, window=w.W, persist_k=w.k,
+                           primary_metric=w.primary, min_signals=w.min_signals, topk=w.topk,
+                           z_threshold=w.thr, direction=tuple(w.directions)))
+
+
+def cpu_baseline(w, x_dev, sample_steps: int) -> dict:
+    """The oracle, as it stands, on the first `sample_steps` steps of the same tensor."""
+    import oracle
+    from gpu_harness import oracle_params
+    xs = x_dev[:sample_steps].cpu().numpy()
+    p = oracle_params(w)
+    t0 = time.perf_counter()
+    oracle.detect(p, xs, topk_k=w.topk, want_z=False)
+    dt = time.perf_counter() - t0
+    return {"value": xs.size / dt, "unit": "samples/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"first {sample_steps} of {w.T} steps ({xs.size} samples, {dt:.2f} s wall)"}
+
+
+def streaming_latency(torch, n_steps: int) -> dict:
+    """Per-call latency of score + window + flags + top-64 with one step appended
+    per call on the 32 768-rank x 8-metric shape, host wall clock incl. stream sync."""
+    from workloads import generate, workload
+    w = workload(4, T=n_steps)
+    x = generate(w, seed=4, device="cuda")
+    det = make_detector(w)
+    out, fl, tk = det.alloc_outputs(1), det.alloc_flags(), det.alloc_topk(w.topk)
+    stream = torch.cuda.Stream()
+    lat = []
+    with torch.cuda.stream(stream):
+        for t in range(n_steps):
+            if t == 50:
+                lat.clear()
+            t0 = time.perf_counter()
+            det.score_batch(x[t:t + 1], out, stream)
+            det.update_window(out, 1, stream=stream)
+            det.flags(fl, stream)
+            det.topk_nodes(w.topk, tk, stream)
+            stream.synchronize()
+            lat.append(time.perf_counter() - t0)
+    lat.sort()
+    det.close()
+    return {"workload": f"{w.R} ranks x {w.M} metrics, 1 step per call, W={w.W}",
+            "calls": len(lat), "p50_us": 1e6 * lat[len(lat) // 2],
+            "p99_us": 1e6 * lat[int(len(lat) * 0.99)]}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--cpu-sample-steps", type=int, default=256)
+    ap.add_argument("--stream-steps", type=int, default=2000)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--no-stream", action="store_true", help="skip the streaming-latency leg")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 "
+              "(the path shards by step across GPUs by design only)", file=sys.stderr)
+        return 2
+    import torch
+    from workloads import generate, workload
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    w = workload(3)
+    x = generate(w, seed=3, device="cuda")          # [T][M][R] fp32, resident in HBM
+    det = make_detector(w)
+    out, fl, tk = det.alloc_outputs(w.T), det.alloc_flags(), det.alloc_topk(w.topk)
+    stream = torch.cuda.Stream()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(a.steps)]
+
+    def step(i, timed):
+        if timed:
+            ev[i][0].record(stream)
+        det.score_batch(x, out, stream)
+        if timed:
+            ev[i][1].record(stream)
+        det.update_window(out, w.T, stream=stream)
+        det.flags(fl, stream)
+        det.topk_nodes(w.topk, tk, stream)
+
+    with torch.cuda.stream(stream):
+        for i in range(a.warmup):
+            step(i, False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(a.steps):
+            step(i, True)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / a.steps
+    score_ms = sum(s.elapsed_time(e) for s, e in ev) / a.steps
+    alg = algorithmic_bytes_per_launch(w.R, w.M, w.T)
+    achieved = alg / (score_ms * 1e-3) / 1e9
+    res = {
+        "metric": "telemetry samples scored/sec", "value": w.samples / (ms_per_step * 1e-3),
+        "unit": "samples/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.R} ranks x {w.T} steps x {w.M} metrics fp32 "
+                               f"(heavy-tailed noise, W={w.W}, k={w.k}, top-{w.topk}); "
+                               "score_batch + update_window + flags + topk_nodes per step"},
+        "roofline": {"bound": "hbm", "kernel": "score_kernel<1024,16>", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes": alg, "avg_launch_ms": score_ms},
+    }
+    if not a.no_cpu:
+        res["cpu_baseline"] = cpu_baseline(w, x, a.cpu_sample_steps)
+    del x, out
+    torch.cuda.empty_cache()
+    if not a.no_stream:
+        res["streaming"] = streaming_latency(torch, a.stream_steps)
+    det.close()
+    print(json.dumps(res))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -57,6 +57,8 @@ def _load():
         vp = ctypes.c_void_p
         _lib.go_score.argtypes = [ctypes.POINTER(_Cfg), vp, ctypes.c_uint64] + [vp] * 10
         _lib.go_score.restype = None
+        _lib.go_num_threads.argtypes = []
+        _lib.go_num_threads.restype = ctypes.c_int
         _lib.go_median.argtypes = [vp, ctypes.c_uint64]
         _lib.go_median.restype = ctypes.c_float
         _lib.go_window.argtypes = [ctypes.c_uint32, vp, ctypes.c_uint64, ctypes.c_uint32,
@@ -131,6 +133,11 @@ class Scores:
 
 def _ptr(a: Optional[np.ndarray]):
     return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def num_threads() -> int:
+    """Threads the oracle's column-parallel loops use."""
+    return int(_load().go_num_threads())
 
 
 def median(v: np.ndarray) -> np.float32:

@@ -28,6 +28,9 @@
 #include <cstdint>
 #include <cstring>
 #include <vector>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 extern "C" {
 
@@ -85,6 +88,15 @@ inline uint32_t order_key(float f) {
 }  // namespace
 
 extern "C" {
+
+// Threads the column-parallel loops will use (columns are independent).
+int go_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 // The median rule on its own (any count >= 1), after reading -0 as +0.
 float go_median(const float* v, uint64_t n) {
