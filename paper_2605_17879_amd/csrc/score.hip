@@ -46,34 +46,37 @@ struct Shared {
     uint32_t cand[CAND_CAP];
     uint32_t wpart[16];
     uint32_t below, ncand;
-    uint32_t qlo, qhi, dlo, dhi;
-    uint32_t res[6];   // ba, prefix before ba, bb, prefix through bb, va, vb
+    uint32_t smin, smax;       // extremes of the sample keys
+    uint32_t umax[2];          // largest raw bit pattern of the column (double-buffered)
+    uint32_t res[6];           // ba, prefix before ba, bb, prefix through bb, va, vb
     uint8_t nodeb[MAX_NODES];
 };
 
-// Cross-lane moves with immediate patterns (DPP, swizzle, permlane): no address
-// registers, nothing for the optimiser to hoist out of the column loop.
+// Cross-lane moves with immediate patterns (DPP): no address registers, nothing
+// for the optimiser to hoist out of the column loop.
 template <int CTRL, int ROW_MASK = 0xF>
 __device__ __forceinline__ uint32_t dpp0(uint32_t v) {   // lanes without a source read 0
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, true);
 }
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ uint32_t dpp_keep(uint32_t v) {   // lanes without a source keep v
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, ROW_MASK, 0xF, false);
+}
 template <int J>
-__device__ __forceinline__ uint32_t lane_xor(uint32_t v, int lane) {
+__device__ __forceinline__ uint32_t lane_xor(uint32_t v) {
     if constexpr (J == 1) return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);
     else if constexpr (J == 2) return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true);
     else if constexpr (J == 8) return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x128, 0xF, 0xF, true);
-    else if constexpr (J == 4 || J == 16) return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x1F | (J << 10));
     else {
-        static_assert(J == 32, "lane_xor");
-        auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
-        return (lane & 32) ? r[0] : r[1];
+        static_assert(J == 4, "lane_xor");
+        return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x1F | (J << 10));
     }
 }
 __device__ __forceinline__ float lane_xor1(float v) {
     return __uint_as_float((uint32_t)__builtin_amdgcn_mov_dpp((int)__float_as_uint(v), 0xB1, 0xF, 0xF, true));
 }
 
-// Inclusive prefix sum across the wave.
+// Inclusive prefix sum across the wave (lane 63 ends with the total).
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
     v += dpp0<0x111>(v);          // row_shr:1
     v += dpp0<0x112>(v);          // row_shr:2
@@ -83,11 +86,25 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
     v += dpp0<0x143, 0xC>(v);     // row_bcast:31 into rows 2 and 3
     return v;
 }
+// Minimum / maximum over the wave, valid in lane 63.
+__device__ __forceinline__ uint32_t wave_min_to_last(uint32_t v) {
+    v = min(v, dpp_keep<0x111>(v)); v = min(v, dpp_keep<0x112>(v));
+    v = min(v, dpp_keep<0x114>(v)); v = min(v, dpp_keep<0x118>(v));
+    v = min(v, dpp_keep<0x142, 0xA>(v)); v = min(v, dpp_keep<0x143, 0xC>(v));
+    return v;
+}
+__device__ __forceinline__ uint32_t wave_max_to_last(uint32_t v) {
+    v = max(v, dpp_keep<0x111>(v)); v = max(v, dpp_keep<0x112>(v));
+    v = max(v, dpp_keep<0x114>(v)); v = max(v, dpp_keep<0x118>(v));
+    v = max(v, dpp_keep<0x142, 0xA>(v)); v = max(v, dpp_keep<0x143, 0xC>(v));
+    return v;
+}
 
 // Exclusive prefix sum of one value per thread over the workgroup; total in *tot.
 template <int NT>
-__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wpart, uint32_t* tot) {
-    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x >> 6;
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t tid, uint32_t* wpart,
+                                                    uint32_t* tot) {
+    const uint32_t lane = tid & (WAVE - 1), w = tid >> 6;
     const uint32_t inc = wave_incl_scan(v);
     if (NT == WAVE) {
         *tot = __builtin_amdgcn_readlane((int)inc, WAVE - 1);
@@ -99,96 +116,167 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wpart,
 #pragma unroll
     for (int i = 0; i < NT / WAVE; ++i) {
         uint32_t p = wpart[i];
-        if (i < w) off += p;
+        if ((uint32_t)i < w) off += p;
         total += p;
     }
     *tot = total;
     return off + inc - v;
 }
 
-template <int K, int J>
-__device__ __forceinline__ uint32_t sort_step(uint32_t v, int lane) {
-    const uint32_t o = lane_xor<J>(v, lane);
-    const bool take_min = ((lane & K) == 0) == ((lane & J) == 0);
-    const uint32_t mn = v < o ? v : o, mx = v < o ? o : v;
-    return take_min ? mn : mx;
-}
-template <int K, int J>
-__device__ __forceinline__ uint32_t sort_merge(uint32_t v, int lane) {
-    v = sort_step<K, J>(v, lane);
-    if constexpr (J > 1) v = sort_merge<K, J / 2>(v, lane);
-    return v;
-}
-// Ascending bitonic sort of one value per lane across the wave.
-__device__ __forceinline__ uint32_t wave_sort(uint32_t v, int lane) {
-    v = sort_merge<2, 1>(v, lane);
-    v = sort_merge<4, 2>(v, lane);
-    v = sort_merge<8, 4>(v, lane);
-    v = sort_merge<16, 8>(v, lane);
-    v = sort_merge<32, 16>(v, lane);
-    v = sort_merge<64, 32>(v, lane);
-    return v;
-}
-
-// A value the optimiser cannot see through: stops it from keeping one pass's
-// per-element temporaries alive for the next pass (64+ registers per lane).
-__device__ __forceinline__ uint32_t opaque(uint32_t v) {
+// Values the optimiser cannot see through.  They stop it from keeping one
+// pass's per-element temporaries, or values derived from the thread index,
+// alive in registers across the whole column loop.
+__device__ __forceinline__ uint32_t opaque_s(uint32_t v) {   // wave-uniform
     v = rfl(v);
     asm volatile("" : "+s"(v));
     return v;
 }
+__device__ __forceinline__ uint32_t opaque_v(uint32_t v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
 
-// Keys of the median selection: the order-preserving image of x itself.
-template <int ROWS>
+// Keys of the median selection.  PLAIN: the column has no sign bit set, so the
+// raw bits order like the values; otherwise the order-preserving image is used.
+template <int ROWS, bool PLAIN>
 struct XKeys {
-    static constexpr bool kSigned = true;
     const float (&v)[ROWS][4];
-    __device__ __forceinline__ uint32_t token() const { return opaque(31u); }
-    __device__ __forceinline__ uint32_t raw(int j, int i, uint32_t) const { return __float_as_uint(v[j][i]); }
-    // full key from the raw bits; tok is an opaque 31
-    __device__ __forceinline__ uint32_t full(uint32_t b, uint32_t tok) const {
-        return b ^ ((uint32_t)((int32_t)b >> tok) | 0x80000000u);
+    __device__ __forceinline__ uint32_t token() const { return opaque_s(31u); }
+    __device__ __forceinline__ uint32_t key(float f, uint32_t tok) const {
+        if (PLAIN) return __float_as_uint(f);
+        // -0 reads as +0; the zero is derived from the opaque token so that the
+        // sum is recomputed per pass instead of being kept for all 64 values
+        const uint32_t b = __float_as_uint(f + __uint_as_float(tok - 31u));
+        return b ^ ((uint32_t)((int32_t)b >> tok) | 0x80000000u);   // tok is an opaque 31
+    }
+    __device__ __forceinline__ uint32_t at(int j, int i, uint32_t tok) const { return key(v[j][i], tok); }
+    __device__ __forceinline__ float value(uint32_t k) const {
+        return PLAIN ? __uint_as_float(k) : float_of_key(k);
     }
 };
 
 // Keys of the MAD selection: the bits of |x - med| (non-negative floats order as integers).
 template <int ROWS>
 struct DKeys {
-    static constexpr bool kSigned = false;
     const float (&v)[ROWS][4];
     float med;
-    __device__ __forceinline__ uint32_t token() const { return opaque(__float_as_uint(med)); }
-    __device__ __forceinline__ uint32_t raw(int j, int i, uint32_t tok) const {
-        return __float_as_uint(fabsf(v[j][i] - __uint_as_float(tok)));
+    __device__ __forceinline__ uint32_t token() const { return opaque_s(__float_as_uint(med)); }
+    __device__ __forceinline__ uint32_t key(float f, uint32_t tok) const {
+        return __float_as_uint(fabsf(f - __uint_as_float(tok)));     // tok is an opaque med
     }
-    __device__ __forceinline__ uint32_t full(uint32_t b, uint32_t) const { return b; }
+    __device__ __forceinline__ uint32_t at(int j, int i, uint32_t tok) const { return key(v[j][i], tok); }
+    __device__ __forceinline__ float value(uint32_t k) const { return __uint_as_float(k); }
 };
 
+// After a counting pass: find the buckets holding ranks ka and kb (relative to
+// everything, `below` keys lie under the histogram's range).  Results in sh.res.
+// Returns whether both ranks fall inside the histogram.  Ends with a barrier.
+template <int NT, int LOG_NB, typename SH>
+__device__ __forceinline__ bool locate(SH& sh, uint32_t tid, uint32_t ka, uint32_t kb,
+                                       uint32_t* total_out) {
+    constexpr int BPT = (1 << LOG_NB) / NT;
+    uint32_t loc[BPT], s = 0;
+#pragma unroll
+    for (int q = 0; q < BPT; ++q) { loc[q] = sh.hist[tid * BPT + q]; s += loc[q]; }
+    uint32_t total;
+    const uint32_t excl = block_excl_scan<NT>(s, tid, sh.wpart, &total);
+    const uint32_t below = sh.below;
+    const uint32_t ra = ka - below, rb = kb - below;   // wrap when not bracketed
+    if (ra - excl < s) {
+        uint32_t p = excl;
+        bool done = false;
+#pragma unroll
+        for (int q = 0; q < BPT; ++q) {
+            if (!done && ra - p < loc[q]) { sh.res[0] = tid * BPT + q; sh.res[1] = p; done = true; }
+            p += loc[q];
+        }
+    }
+    if (rb - excl < s) {
+        uint32_t p = excl;
+        bool done = false;
+#pragma unroll
+        for (int q = 0; q < BPT; ++q) {
+            if (!done && rb - p < loc[q]) { sh.res[2] = tid * BPT + q; sh.res[3] = p + loc[q]; done = true; }
+            p += loc[q];
+        }
+    }
+    __syncthreads();
+    *total_out = total;
+    return rfl(ka >= below && rb < total) != 0;
+}
+
+template <int LOG_NB>
+__device__ __forceinline__ int shift_for(uint32_t span) {
+    const int width = 32 - __builtin_clz(span | 1u);
+    return width > LOG_NB ? width - LOG_NB : 0;            // (span >> shift) < NB
+}
+
 // Exact selection of the order statistics k0 <= k1 (0-based, k1 - k0 <= 1) of
-// ROWS*4 keys per thread held in registers.  [lo, hi] is a guess of a key range
-// containing both; any guess is safe.  Keys of padding lanes (NaN) compare
-// above every real key.  While the range holds only non-negative floats the
-// key arithmetic is done on the raw bits (key - lo is the same number).
+// the ROWS*4 keys per thread held in registers (padding keys compare above all
+// real ones).
+//   1. One sampled key per thread (skey, svalid) goes into a histogram over the
+//      sample's own range; the sample ranks n/2 -+ 2*sqrt(n) give a bracket
+//      [lo, hi] that holds the wanted ranks with high probability and only a
+//      small share of the column.
+//   2. Counting pass: keys inside the bracket go into the LDS histogram, keys
+//      below it are counted.  If the wanted ranks are not inside, count again
+//      over the full range.
+//   3. The buckets holding the ranks are gathered into LDS and ranked exactly,
+//      or, when they are crowded (ties), the range is narrowed to the bucket.
 template <int NT, int ROWS, int LOG_NB, typename SH, typename Keys>
-__device__ __forceinline__ void block_select(SH& sh, const Keys& keys, uint32_t k0, uint32_t k1,
-                                             uint32_t lo, uint32_t hi, uint32_t* out0,
+__device__ __forceinline__ void block_select(SH& sh, const Keys& keys, uint32_t skey, bool svalid,
+                                             uint32_t k0, uint32_t k1, uint32_t* out0,
                                              uint32_t* out1) {
     constexpr int NB = 1 << LOG_NB;
     constexpr int BPT = NB / NT;
     static_assert(BPT >= 1 && (BPT % 4 == 0 || BPT < 4), "bucket split");
-    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    uint32_t lo, hi;
+    {   // ---- bracket from the sample
+        const uint32_t tid = opaque_v(threadIdx.x), lane = tid & (WAVE - 1);
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < BPT; ++q) sh.hist[tid * BPT + q] = 0;
+        if (tid == 0) { sh.below = 0; sh.smin = 0xFFFFFFFFu; sh.smax = 0; }
+        __syncthreads();
+        const uint32_t mn = wave_min_to_last(svalid ? skey : 0xFFFFFFFFu);
+        const uint32_t mx = wave_max_to_last(svalid ? skey : 0u);
+        if (lane == WAVE - 1) { atomicMin(&sh.smin, mn); atomicMax(&sh.smax, mx); }
+        __syncthreads();
+        const uint32_t smin = rfl(sh.smin), smax = rfl(sh.smax);
+        const uint32_t sspan = smax - smin;                 // smin <= smax: some sample is valid
+        const int sshift = shift_for<LOG_NB>(sspan);
+        if (svalid) atomicAdd(&sh.hist[(skey - smin) >> sshift], 1u);
+        __syncthreads();
+        uint32_t n;
+        // total count first (n), then the two sample ranks
+        {
+            uint32_t s = 0;
+#pragma unroll
+            for (int q = 0; q < BPT; ++q) s += sh.hist[tid * BPT + q];
+            (void)block_excl_scan<NT>(s, tid, sh.wpart, &n);
+            __syncthreads();
+        }
+        const uint32_t delta = (uint32_t)(2.0f * __builtin_sqrtf((float)n)) + 1u;
+        const uint32_t half = n / 2;
+        const uint32_t ra = half > delta ? half - 1 - delta : 0u;
+        const uint32_t rb = min(n - 1, half + delta);
+        uint32_t tot;
+        (void)locate<NT, LOG_NB>(sh, tid, ra, rb, &tot);
+        const uint32_t ba = rfl(sh.res[0]), bb = rfl(sh.res[2]);
+        lo = ra == 0 ? 0u : smin + (ba << sshift);
+        const uint64_t hend = (uint64_t)smin + ((uint64_t)(bb + 1) << sshift) - 1;
+        hi = rb == n - 1 ? 0xFFFFFFFFu : (hend > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)hend);
+    }
     // mode 0: both statistics together; 1: k0 alone; 2: k1 alone (after a split)
     int mode = 0;
     uint32_t ka = k0, kb = k1, v0 = 0, v1 = 0;
-    lo = rfl(lo);
-    hi = rfl(hi);
-    if (lo > hi) { lo = 0; hi = 0xFFFFFFFFu; }
     for (;;) {
         const uint32_t span = hi - lo;
-        const int width = 32 - __builtin_clz(span | 1u);           // bits of span
-        const int shift = width > LOG_NB ? width - LOG_NB : 0;      // (span >> shift) < NB
-        const bool plain = !Keys::kSigned || lo >= 0x80000000u;     // raw-bit arithmetic is valid
-        const uint32_t flip = Keys::kSigned ? 0x80000000u : 0u;
+        const int shift = shift_for<LOG_NB>(span);
+        // a fresh copy of the thread index per round: values derived from it (bucket
+        // slots, LDS addresses) are then recomputed instead of living in registers
+        const uint32_t tid = opaque_v(threadIdx.x);
+        const uint32_t lane = tid & (WAVE - 1);
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < BPT; ++q) sh.hist[tid * BPT + q] = 0;
@@ -198,70 +286,29 @@ __device__ __forceinline__ void block_select(SH& sh, const Keys& keys, uint32_t 
         uint32_t nbelow = 0;   // per lane; summed over the wave after the pass
         {
             const uint32_t tok = keys.token();
-            if (plain) {
-                const uint32_t lor = lo ^ flip;
 #pragma unroll
-                for (int j = 0; j < ROWS; ++j) {
+            for (int j = 0; j < ROWS; ++j) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const uint32_t b = keys.raw(j, i, tok);
-                        nbelow += (int32_t)b < (int32_t)lor ? 1u : 0u;
-                        const uint32_t t = b - lor;
-                        if (t <= span) atomicAdd(&sh.hist[t >> shift], 1u);
-                    }
-                    asm volatile("" : "+v"(nbelow));
-                    __builtin_amdgcn_sched_barrier(0);
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t kk = keys.at(j, i, tok);
+                    nbelow += kk < lo ? 1u : 0u;
+                    const uint32_t t = kk - lo;
+                    if (t <= span) atomicAdd(&sh.hist[t >> shift], 1u);
                 }
-            } else {
-#pragma unroll
-                for (int j = 0; j < ROWS; ++j) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const uint32_t kk = keys.full(keys.raw(j, i, tok), tok);
-                        nbelow += kk < lo ? 1u : 0u;
-                        const uint32_t t = kk - lo;
-                        if (t <= span) atomicAdd(&sh.hist[t >> shift], 1u);
-                    }
-                    asm volatile("" : "+v"(nbelow));
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+                asm volatile("" : "+v"(nbelow));
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         nbelow = wave_incl_scan(nbelow);
         if (lane == WAVE - 1 && nbelow) atomicAdd(&sh.below, nbelow);
         __syncthreads();
-        // locate the buckets of ka and kb
-        uint32_t loc[BPT], s = 0;
-#pragma unroll
-        for (int q = 0; q < BPT; ++q) { loc[q] = sh.hist[tid * BPT + q]; s += loc[q]; }
         uint32_t total;
-        const uint32_t excl = block_excl_scan<NT>(s, sh.wpart, &total);
-        const uint32_t below = sh.below;
-        const uint32_t ra = ka - below, rb = kb - below;   // wraps when not bracketed
-        if (ra - excl < s) {
-            uint32_t p = excl;
-            bool done = false;
-#pragma unroll
-            for (int q = 0; q < BPT; ++q) {
-                if (!done && ra - p < loc[q]) { sh.res[0] = tid * BPT + q; sh.res[1] = p; done = true; }
-                p += loc[q];
-            }
-        }
-        if (rb - excl < s) {
-            uint32_t p = excl;
-            bool done = false;
-#pragma unroll
-            for (int q = 0; q < BPT; ++q) {
-                if (!done && rb - p < loc[q]) { sh.res[2] = tid * BPT + q; sh.res[3] = p + loc[q]; done = true; }
-                p += loc[q];
-            }
-        }
-        __syncthreads();
-        const bool bracketed = rfl(ka >= below && rb < total);
-        if (!bracketed) {               // the guess missed: count over all keys
+        const bool bracketed = locate<NT, LOG_NB>(sh, tid, ka, kb, &total);
+        if (!bracketed) {               // the bracket missed: count over all keys
             lo = 0; hi = 0xFFFFFFFFu;
             continue;
         }
+        const uint32_t below = rfl(sh.below);
         const uint32_t ba = rfl(sh.res[0]), pa = rfl(sh.res[1]);
         const uint32_t bb = rfl(sh.res[2]), pb = rfl(sh.res[3]);
         uint32_t va, vb;
@@ -274,37 +321,21 @@ __device__ __forceinline__ void block_select(SH& sh, const Keys& keys, uint32_t 
             const uint32_t chi = cend > hi ? hi : (uint32_t)cend;
             const uint32_t cspan = chi - clo;
             const uint32_t tok = keys.token();
-            if (plain) {
-                const uint32_t clor = clo ^ flip;
 #pragma unroll
-                for (int j = 0; j < ROWS; ++j) {
+            for (int j = 0; j < ROWS; ++j) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const uint32_t b = keys.raw(j, i, tok);
-                        if (b - clor <= cspan) {
-                            uint32_t pos = atomicAdd(&sh.ncand, 1u);
-                            if (pos < (uint32_t)CAND_CAP) sh.cand[pos] = b;   // raw bits: same order as keys here
-                        }
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t kk = keys.at(j, i, tok);
+                    if (kk - clo <= cspan) {
+                        uint32_t pos = atomicAdd(&sh.ncand, 1u);
+                        if (pos < (uint32_t)CAND_CAP) sh.cand[pos] = kk;
                     }
-                    __builtin_amdgcn_sched_barrier(0);
                 }
-            } else {
-#pragma unroll
-                for (int j = 0; j < ROWS; ++j) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const uint32_t kk = keys.full(keys.raw(j, i, tok), tok);
-                        if (kk - clo <= cspan) {
-                            uint32_t pos = atomicAdd(&sh.ncand, 1u);
-                            if (pos < (uint32_t)CAND_CAP) sh.cand[pos] = kk;
-                        }
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+                __builtin_amdgcn_sched_barrier(0);
             }
             __syncthreads();
             const uint32_t cnt = min(sh.ncand, (uint32_t)CAND_CAP);
-            const uint32_t wa = ra - pa, wb = rb - pa;
+            const uint32_t wa = ka - below - pa, wb = kb - below - pa;
             for (uint32_t i = tid; i < cnt; i += NT) {
                 const uint32_t c = sh.cand[i];
                 uint32_t r = 0;
@@ -316,7 +347,7 @@ __device__ __forceinline__ void block_select(SH& sh, const Keys& keys, uint32_t 
                 if (r == wb) sh.res[5] = c;
             }
             __syncthreads();
-            va = rfl(sh.res[4]) ^ (plain ? flip : 0u); vb = rfl(sh.res[5]) ^ (plain ? flip : 0u);
+            va = rfl(sh.res[4]); vb = rfl(sh.res[5]);
         } else {
             // crowded (ties): look inside bucket ba; if the two statistics sit in
             // different crowded buckets, finish k0 first, then k1 on its own
@@ -336,7 +367,8 @@ __device__ __forceinline__ void block_select(SH& sh, const Keys& keys, uint32_t 
     *out1 = v1;
 }
 
-// z' and node score of one register row; AGG 0 = scaled pairwise sum, 1 = max.
+// Signed score and node score of one register row, dividing with the IEEE
+// operator.  AGG 0 = scaled pairwise sum, 1 = max.
 template <int AGG>
 __device__ __forceinline__ void score_row(const float (&x)[4], float med, float s, uint32_t absmask,
                                           uint32_t sgnmask, float thr, float node_scale,
@@ -344,7 +376,7 @@ __device__ __forceinline__ void score_row(const float (&x)[4], float med, float 
     float zs[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const float z = (x[i] - med) / s;
+        const float z = ((x[i] + 0.0f) - med) / s;      // -0 reads as +0
         zs[i] = __uint_as_float((__float_as_uint(z) & absmask) ^ sgnmask);
     }
     uint32_t bits = 0;
@@ -363,6 +395,37 @@ __device__ __forceinline__ void score_row(const float (&x)[4], float med, float 
     }
 }
 
+// The same for the scaled sum, with the quotient d/s obtained from the
+// column's reciprocal r = RN(1/s) by two residual corrections:
+//   q0 = RN(d*r); q1 = RN(q0 + RN(d - q0*s)*r); q2 = RN(q1 + (d - q1*s)*r)
+// q1 is within one ulp of d/s, for which the residual d - q1*s is exact in
+// fp32 and the second correction returns the correctly rounded quotient
+// (Markstein's division theorem), provided nothing under- or overflows --
+// the caller checks the column's magnitudes for that.  ss is +s or -s (a
+// lower-is-worse metric scores -z), TWO_SIDED scores |z|.
+template <bool TWO_SIDED>
+__device__ __forceinline__ void score_row_fast(const float (&x)[4], float med, float ss, float rs,
+                                               float thr, float node_scale, uint32_t* e, float* nz) {
+    float zs[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float d = x[i] - med;
+        const float q0 = d * rs;
+        const float e0 = __builtin_fmaf(-q0, ss, d);
+        const float q1 = __builtin_fmaf(e0, rs, q0);
+        const float e1 = __builtin_fmaf(-q1, ss, d);
+        const float q2 = __builtin_fmaf(e1, rs, q1);
+        zs[i] = TWO_SIDED ? fabsf(q2) : q2;
+    }
+    uint32_t bits = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) bits |= (zs[i] > thr ? 1u : 0u) << (8 * i);
+    *e = bits;
+    const float half = (zs[0] + zs[1]) + (zs[2] + zs[3]);
+    const float other = lane_xor1(half);
+    *nz = node_scale * (half + other);
+}
+
 // FULL: R == NT*4*ROWS exactly, so no lane is padding and no bounds are checked.
 template <int NT, int ROWS, int LOG_NB, bool FULL>
 __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
@@ -370,7 +433,11 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
     constexpr int MAX_NODES = BLK * ROWS / 8;
     constexpr int NWAVES = NT / WAVE;
     using SH = Shared<NT, LOG_NB, MAX_NODES>;
-    __shared__ SH sh;
+    // Dynamic LDS: the selection's work area, then one word of exceed-mask bytes
+    // per (row, thread) -- kept in LDS, not registers, across the M columns.
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    SH& sh = *reinterpret_cast<SH*>(lds_raw);
+    uint32_t* emask = reinterpret_cast<uint32_t*>(lds_raw + ((sizeof(SH) + 15) & ~(size_t)15));
 
     const int tid = threadIdx.x, lane = tid & (WAVE - 1);
     const int w = rfl(tid >> 6);
@@ -387,18 +454,15 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
     auto rbase = [&](int j, uint32_t tid4) -> uint32_t {
         return (uint32_t)((j + w) & (ROWS - 1)) * BLK + tid4;
     };
-    auto fresh_tid4 = [&]() -> uint32_t {
-        uint32_t v = (uint32_t)tid * 4;
-        asm volatile("" : "+v"(v));
-        return v;
-    };
+    auto fresh_tid4 = [&]() -> uint32_t { return opaque_v((uint32_t)tid * 4); };
 
-    uint32_t E[ROWS];            // exceed mask bytes of the lane's 4 ranks per row
     uint32_t NE[(ROWS + 3) / 4]; // node mask byte per row, packed
 #pragma unroll
-    for (int j = 0; j < ROWS; ++j) E[j] = 0;
+    for (int j = 0; j < ROWS; ++j) emask[j * NT + tid] = 0;   // each slot is private to its thread
 #pragma unroll
     for (int j = 0; j < (ROWS + 3) / 4; ++j) NE[j] = 0;
+    if (tid == 0) { sh.umax[0] = 0; sh.umax[1] = 0; }
+    __syncthreads();
 
     const uint32_t k0 = R / 2 - 1, k1 = R / 2;   // R is even
 
@@ -417,48 +481,37 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
             }
             v[j][0] = q.x; v[j][1] = q.y; v[j][2] = q.z; v[j][3] = q.w;
         }
-        if (tid == 0) { sh.qlo = 0xFFFFFFFFu; sh.qhi = 0; sh.dlo = 0xFFFFFFFFu; sh.dhi = 0; }
-        __syncthreads();
-        // -0 reads as +0 (x + 0 is exact for everything else)
+        const bool svalid = FULL || rbase(0, tl) < R;
+        // Largest raw bit pattern of the column: >= 0x80000000 iff some value carries
+        // a sign bit (negative or -0); otherwise it is the bit pattern of the maximum.
+        uint32_t um = 0;
 #pragma unroll
         for (int j = 0; j < ROWS; ++j) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) v[j][i] += 0.0f;
-        }
-        // bracket the median from a sorted per-wave sample of row 0
-        const bool svalid = FULL || rbase(0, tl) < R;
-        const uint32_t nv = __popcll(__ballot(svalid));
-        int lane_o = lane;                       // recomputed per column, so that the sort's
-        asm volatile("" : "+v"(lane_o));         // lane predicates are not kept in registers
-        const uint32_t sorted = wave_sort(svalid ? key_of(v[0][0]) : 0xFFFFFFFFu, lane_o);
-        auto pick = [&](uint32_t idx) { return (uint32_t)__builtin_amdgcn_readlane((int)sorted, (int)rfl(idx)); };
-        if (nv > 0) {
-            const uint32_t q1 = pick(nv / 4);
-            const uint32_t q3 = pick(min(nv - 1, (3 * nv) / 4));
-            if (lane == 0) { atomicMin(&sh.qlo, q1); atomicMax(&sh.qhi, q3); }
-        }
-        __syncthreads();
-        uint32_t s0, s1;
-        block_select<NT, ROWS, LOG_NB>(sh, XKeys<ROWS>{v}, k0, k1, sh.qlo, sh.qhi, &s0, &s1);
-        const float med = 0.5f * (float_of_key(s0) + float_of_key(s1));
-
-        // bracket the MAD from the same sorted sample: inner and outer distances
-        if (nv > 0) {
-            const float fil = float_of_key(pick((3 * nv) / 8));
-            const float fih = float_of_key(pick(min(nv - 1, (5 * nv) / 8)));
-            const float fol = float_of_key(pick((5 * nv) / 32));
-            const float foh = float_of_key(pick(min(nv - 1, (27 * nv) / 32)));
-            float inner = fminf(med - fil, fih - med);
-            float outer = fmaxf(med - fol, foh - med);
-            inner = inner > 0.0f ? inner : 0.0f;
-            outer = outer > 0.0f ? outer : 0.0f;
-            if (lane == 0) {
-                atomicMin(&sh.dlo, __float_as_uint(inner));
-                atomicMax(&sh.dhi, __float_as_uint(outer));
+            if (FULL || rbase(j, tl) < R) {
+                um = max(um, max(__float_as_uint(v[j][0]), __float_as_uint(v[j][1])));
+                um = max(um, max(__float_as_uint(v[j][2]), __float_as_uint(v[j][3])));
             }
         }
+        um = wave_max_to_last(um);
+        if (lane == WAVE - 1) atomicMax(&sh.umax[m & 1], um);
         __syncthreads();
-        block_select<NT, ROWS, LOG_NB>(sh, DKeys<ROWS>{v, med}, k0, k1, sh.dlo, sh.dhi, &s0, &s1);
+        if (tid == 0) sh.umax[(m + 1) & 1] = 0;
+        const uint32_t umax = rfl(sh.umax[m & 1]);
+        const bool signs = umax >= 0x80000000u;
+
+        uint32_t s0, s1;
+        float med;
+        if (!signs) {
+            block_select<NT, ROWS, LOG_NB>(sh, XKeys<ROWS, true>{v}, __float_as_uint(v[0][0]), svalid,
+                                           k0, k1, &s0, &s1);
+            med = 0.5f * (__uint_as_float(s0) + __uint_as_float(s1));
+        } else {
+            block_select<NT, ROWS, LOG_NB>(sh, XKeys<ROWS, false>{v}, key_of(v[0][0] + 0.0f), svalid,
+                                           k0, k1, &s0, &s1);
+            med = 0.5f * (float_of_key(s0) + float_of_key(s1));
+        }
+        block_select<NT, ROWS, LOG_NB>(sh, DKeys<ROWS>{v, med}, __float_as_uint(fabsf(v[0][0] - med)),
+                                       svalid, k0, k1, &s0, &s1);
         const float mad = 0.5f * (__uint_as_float(s0) + __uint_as_float(s1));
         if (tid == 0) {
             a.med[t * M + m] = med;
@@ -470,35 +523,62 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
 
         // z, exceedance and node scores
         const int dir = a.dir[m];
-        const uint32_t absmask = dir == 0 ? 0x7FFFFFFFu : 0xFFFFFFFFu;
-        const uint32_t sgnmask = dir < 0 ? 0x80000000u : 0u;
         const bool prim = m == a.primary;
         const uint32_t tz = fresh_tid4();
         float* nzrow = a.node_z + t * N;
-        auto zphase = [&](auto agg) {
+        // The reciprocal route is exact while no intermediate can leave the normal
+        // range: all x in [0, 2^59], 2^-34 <= med, 2^-60 <= s <= 2^60 (then every
+        // non-zero |x - med| lies in [2^-59, 2^59]).
+        const bool fast = !signs && a.node_agg == 0 && umax <= 0x5D000000u && med >= 0x1p-34f &&
+                          s >= 0x1p-60f && s <= 0x1p60f;
+        if (fast) {
+            const float ss = dir < 0 ? -s : s;
+            const float rs = 1.0f / ss;
+            auto zfast = [&](auto two_sided) {
 #pragma unroll
-            for (int j = 0; j < ROWS; ++j) {
-                uint32_t e;
-                float nz;
-                score_row<decltype(agg)::value>(v[j], med, s, absmask, sgnmask, thr, a.node_scale, &e, &nz);
-                E[j] |= e << m;
-                NE[j / 4] |= (nz > thr ? 1u : 0u) << (8 * (j & 3) + m);
-                if (prim && (FULL || rbase(j, tz) < R) && !(tz & 4)) nzrow[rbase(j, tz) / 8] = nz;
-                // pin the row's results here, or its scores stay live until the loop ends
-                asm volatile("" : "+v"(E[j]), "+v"(NE[j / 4]));
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        };
-        if (a.node_agg == 0) zphase(std::integral_constant<int, 0>{});
-        else zphase(std::integral_constant<int, 1>{});
-        if (a.z) {   // optional full z output, recomputed so that the loop above stays lean
+                for (int j = 0; j < ROWS; ++j) {
+                    uint32_t e;
+                    float nz;
+                    score_row_fast<decltype(two_sided)::value>(v[j], med, ss, rs, thr, a.node_scale, &e, &nz);
+                    __hip_atomic_fetch_or(&emask[j * NT + tz / 4], e << m, __ATOMIC_RELAXED,
+                                          __HIP_MEMORY_SCOPE_WORKGROUP);
+                    NE[j / 4] |= (nz > thr ? 1u : 0u) << (8 * (j & 3) + m);
+                    if (prim && (FULL || rbase(j, tz) < R) && !(tz & 4)) nzrow[rbase(j, tz) / 8] = nz;
+                    // pin the row's results here, or its scores stay live until the loop ends
+                    asm volatile("" : "+v"(NE[j / 4]));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            if (dir != 0) zfast(std::false_type{});
+            else zfast(std::true_type{});
+        } else {
+            const uint32_t absmask = dir == 0 ? 0x7FFFFFFFu : 0xFFFFFFFFu;
+            const uint32_t sgnmask = dir < 0 ? 0x80000000u : 0u;
+            auto zphase = [&](auto agg) {
+#pragma unroll
+                for (int j = 0; j < ROWS; ++j) {
+                    uint32_t e;
+                    float nz;
+                    score_row<decltype(agg)::value>(v[j], med, s, absmask, sgnmask, thr, a.node_scale, &e, &nz);
+                    __hip_atomic_fetch_or(&emask[j * NT + tz / 4], e << m, __ATOMIC_RELAXED,
+                                          __HIP_MEMORY_SCOPE_WORKGROUP);
+                    NE[j / 4] |= (nz > thr ? 1u : 0u) << (8 * (j & 3) + m);
+                    if (prim && (FULL || rbase(j, tz) < R) && !(tz & 4)) nzrow[rbase(j, tz) / 8] = nz;
+                    asm volatile("" : "+v"(NE[j / 4]));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            if (a.node_agg == 0) zphase(std::integral_constant<int, 0>{});
+            else zphase(std::integral_constant<int, 1>{});
+        }
+        if (a.z) {   // optional full z output, recomputed so that the loops above stay lean
             float* zcol = a.z + (t * M + m) * (size_t)R;
 #pragma unroll
             for (int j = 0; j < ROWS; ++j) {
                 if (FULL || rbase(j, tz) < R) {
                     float4 q;
-                    q.x = (v[j][0] - med) / s; q.y = (v[j][1] - med) / s;
-                    q.z = (v[j][2] - med) / s; q.w = (v[j][3] - med) / s;
+                    q.x = ((v[j][0] + 0.0f) - med) / s; q.y = ((v[j][1] + 0.0f) - med) / s;
+                    q.z = ((v[j][2] + 0.0f) - med) / s; q.w = ((v[j][3] + 0.0f) - med) / s;
                     *reinterpret_cast<float4*>(zcol + rbase(j, tz)) = q;
                 }
             }
@@ -512,11 +592,12 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
         const bool valid = FULL || rbase(j, to) < R;
-        if (valid) *reinterpret_cast<uint32_t*>(erow + rbase(j, to)) = E[j];
+        const uint32_t Ej = emask[j * NT + to / 4];
+        if (valid) *reinterpret_cast<uint32_t*>(erow + rbase(j, to)) = Ej;
         uint32_t nib = 0;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const uint32_t b = (E[j] >> (8 * i)) & 0xFFu;
+            const uint32_t b = (Ej >> (8 * i)) & 0xFFu;
             const bool an = ((b >> a.primary) & 1u) && (uint32_t)__popc(b) >= a.min_signals;
             nib |= (an && valid ? 1u : 0u) << i;
         }
@@ -524,10 +605,10 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
         const int sub = lane & 15;
         uint32_t wlo = sub < 8 ? nib << (4 * sub) : 0u;
         uint32_t whi = sub >= 8 ? nib << (4 * (sub - 8)) : 0u;
-        wlo |= lane_xor<1>(wlo, lane); whi |= lane_xor<1>(whi, lane);
-        wlo |= lane_xor<2>(wlo, lane); whi |= lane_xor<2>(whi, lane);
-        wlo |= lane_xor<4>(wlo, lane); whi |= lane_xor<4>(whi, lane);
-        wlo |= lane_xor<8>(wlo, lane); whi |= lane_xor<8>(whi, lane);
+        wlo |= lane_xor<1>(wlo); whi |= lane_xor<1>(whi);
+        wlo |= lane_xor<2>(wlo); whi |= lane_xor<2>(whi);
+        wlo |= lane_xor<4>(wlo); whi |= lane_xor<4>(whi);
+        wlo |= lane_xor<8>(wlo); whi |= lane_xor<8>(whi);
         if (sub == 0 && valid)
             arow[rbase(j, to) / 64] = ((uint64_t)whi << 32) | wlo;
         if (valid && !(to & 4)) sh.nodeb[rbase(j, to) / 8] = (uint8_t)((NE[j / 4] >> (8 * (j & 3))) & 0xFFu);
@@ -546,13 +627,27 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
     }
 }
 
+template <int NT, int ROWS, int LOG_NB, bool FULL>
+hipError_t launch_one(const gd_score_args& a, hipStream_t s) {
+    using SH = Shared<NT, LOG_NB, NT * 4 * ROWS / 8>;
+    constexpr size_t lds = ((sizeof(SH) + 15) & ~(size_t)15) + (size_t)ROWS * NT * 4;
+    static_assert(lds <= 160 * 1024, "LDS budget of one CU");
+    auto kern = score_kernel<NT, ROWS, LOG_NB, FULL>;
+    static bool configured = false;      // a handle is single-threaded; a repeated set is harmless
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(a.T), dim3(NT), lds, s, a);
+    return hipGetLastError();
+}
+
 template <int NT, int ROWS, int LOG_NB>
 hipError_t launch(const gd_score_args& a, hipStream_t s) {
-    if (a.R == (uint32_t)NT * 4 * ROWS)
-        hipLaunchKernelGGL((score_kernel<NT, ROWS, LOG_NB, true>), dim3(a.T), dim3(NT), 0, s, a);
-    else
-        hipLaunchKernelGGL((score_kernel<NT, ROWS, LOG_NB, false>), dim3(a.T), dim3(NT), 0, s, a);
-    return hipGetLastError();
+    if (a.R == (uint32_t)NT * 4 * ROWS) return launch_one<NT, ROWS, LOG_NB, true>(a, s);
+    return launch_one<NT, ROWS, LOG_NB, false>(a, s);
 }
 
 }  // namespace
