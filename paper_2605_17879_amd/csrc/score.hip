@@ -112,13 +112,12 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t tid, ui
     }
     if (lane == WAVE - 1) wpart[w] = inc;
     __syncthreads();
-    uint32_t off = 0, total = 0;
-#pragma unroll
-    for (int i = 0; i < NT / WAVE; ++i) {
-        uint32_t p = wpart[i];
-        if ((uint32_t)i < w) off += p;
-        total += p;
-    }
+    // every wave scans the (at most 16) wave totals itself: one LDS read, a row scan
+    uint32_t p = lane < (uint32_t)(NT / WAVE) ? wpart[lane] : 0u;
+    p += dpp0<0x111>(p); p += dpp0<0x112>(p); p += dpp0<0x114>(p); p += dpp0<0x118>(p);
+    const uint32_t total = __builtin_amdgcn_readlane((int)p, NT / WAVE - 1);
+    const uint32_t wu = rfl(w);
+    const uint32_t off = wu ? (uint32_t)__builtin_amdgcn_readlane((int)p, (int)(wu - 1)) : 0u;
     *tot = total;
     return off + inc - v;
 }
@@ -214,7 +213,7 @@ __device__ __forceinline__ int shift_for(uint32_t span) {
 // Exact selection of the order statistics k0 <= k1 (0-based, k1 - k0 <= 1) of
 // the ROWS*4 keys per thread held in registers (padding keys compare above all
 // real ones).
-//   1. One sampled key per thread (skey, svalid) goes into a histogram over the
+//   1. One sampled key per thread (skey, svalid; n of them valid) goes into a histogram over the
 //      sample's own range; the sample ranks n/2 -+ 2*sqrt(n) give a bracket
 //      [lo, hi] that holds the wanted ranks with high probability and only a
 //      small share of the column.
@@ -225,7 +224,7 @@ __device__ __forceinline__ int shift_for(uint32_t span) {
 //      or, when they are crowded (ties), the range is narrowed to the bucket.
 template <int NT, int ROWS, int LOG_NB, typename SH, typename Keys>
 __device__ __forceinline__ void block_select(SH& sh, const Keys& keys, uint32_t skey, bool svalid,
-                                             uint32_t k0, uint32_t k1, uint32_t* out0,
+                                             uint32_t n, uint32_t k0, uint32_t k1, uint32_t* out0,
                                              uint32_t* out1) {
     constexpr int NB = 1 << LOG_NB;
     constexpr int BPT = NB / NT;
@@ -247,15 +246,7 @@ __device__ __forceinline__ void block_select(SH& sh, const Keys& keys, uint32_t 
         const int sshift = shift_for<LOG_NB>(sspan);
         if (svalid) atomicAdd(&sh.hist[(skey - smin) >> sshift], 1u);
         __syncthreads();
-        uint32_t n;
-        // total count first (n), then the two sample ranks
-        {
-            uint32_t s = 0;
-#pragma unroll
-            for (int q = 0; q < BPT; ++q) s += sh.hist[tid * BPT + q];
-            (void)block_excl_scan<NT>(s, tid, sh.wpart, &n);
-            __syncthreads();
-        }
+        // n valid samples: the ranks n/2 -+ (2*sqrt(n) + 1) bracket the column's median
         const uint32_t delta = (uint32_t)(2.0f * __builtin_sqrtf((float)n)) + 1u;
         const uint32_t half = n / 2;
         const uint32_t ra = half > delta ? half - 1 - delta : 0u;
@@ -426,6 +417,34 @@ __device__ __forceinline__ void score_row_fast(const float (&x)[4], float med, f
     *nz = node_scale * (half + other);
 }
 
+// Supporting (non-primary) metric with a one-sided direction, sign-free column:
+// only the decisions are needed, not the scores, so no division is done.
+//   * A rank exceeds iff x >= xstar (higher is worse) or x <= xstar (lower is
+//     worse): sub and divide are monotone, and xstar is the exact boundary found
+//     by the caller with the very operations the definition uses.
+//   * The node score scale*sum(z') is estimated as cc*sum(x) - kk with
+//     cc ~ +-scale/s and kk ~ 8*med*cc.  All roundings of the exact chain and of
+//     the estimate together stay below `margin` (see the caller), so the estimate
+//     decides unless it falls within `margin` of the threshold; then *near is set
+//     for the lane and the caller evaluates the row exactly.
+template <bool LOWER_IS_WORSE>
+__device__ __forceinline__ void score_row_decide(const float (&x)[4], float xstar, float cc, float kk,
+                                                 float thr, float margin, uint32_t* e, float* nz,
+                                                 bool* near) {
+    uint32_t bits = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const bool ex = LOWER_IS_WORSE ? x[i] <= xstar : x[i] >= xstar;
+        bits |= (ex ? 1u : 0u) << (8 * i);
+    }
+    *e = bits;
+    const float half = (x[0] + x[1]) + (x[2] + x[3]);
+    const float sum = half + lane_xor1(half);
+    const float est = __builtin_fmaf(sum, cc, -kk);
+    *nz = est;
+    *near = fabsf(est - thr) <= margin;
+}
+
 // FULL: R == NT*4*ROWS exactly, so no lane is padding and no bounds are checked.
 template <int NT, int ROWS, int LOG_NB, bool FULL>
 __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
@@ -461,8 +480,16 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
     for (int j = 0; j < ROWS; ++j) emask[j * NT + tid] = 0;   // each slot is private to its thread
 #pragma unroll
     for (int j = 0; j < (ROWS + 3) / 4; ++j) NE[j] = 0;
-    if (tid == 0) { sh.umax[0] = 0; sh.umax[1] = 0; }
+    if (tid == 0) { sh.umax[0] = 0; sh.umax[1] = 0; sh.ncand = 0; }
     __syncthreads();
+    // number of threads whose sampled element (row 0) is a real rank
+    uint32_t nsample = NT;
+    if (!FULL) {
+        const uint32_t c = __popcll(__ballot(rbase(0, (uint32_t)tid * 4) < R));
+        if (lane == 0) atomicAdd(&sh.ncand, c);
+        __syncthreads();
+        nsample = rfl(sh.ncand);
+    }
 
     const uint32_t k0 = R / 2 - 1, k1 = R / 2;   // R is even
 
@@ -503,15 +530,15 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
         float med;
         if (!signs) {
             block_select<NT, ROWS, LOG_NB>(sh, XKeys<ROWS, true>{v}, __float_as_uint(v[0][0]), svalid,
-                                           k0, k1, &s0, &s1);
+                                           nsample, k0, k1, &s0, &s1);
             med = 0.5f * (__uint_as_float(s0) + __uint_as_float(s1));
         } else {
             block_select<NT, ROWS, LOG_NB>(sh, XKeys<ROWS, false>{v}, key_of(v[0][0] + 0.0f), svalid,
-                                           k0, k1, &s0, &s1);
+                                           nsample, k0, k1, &s0, &s1);
             med = 0.5f * (float_of_key(s0) + float_of_key(s1));
         }
         block_select<NT, ROWS, LOG_NB>(sh, DKeys<ROWS>{v, med}, __float_as_uint(fabsf(v[0][0] - med)),
-                                       svalid, k0, k1, &s0, &s1);
+                                       svalid, nsample, k0, k1, &s0, &s1);
         const float mad = 0.5f * (__uint_as_float(s0) + __uint_as_float(s1));
         if (tid == 0) {
             a.med[t * M + m] = med;
@@ -531,9 +558,58 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
         // non-zero |x - med| lies in [2^-59, 2^59]).
         const bool fast = !signs && a.node_agg == 0 && umax <= 0x5D000000u && med >= 0x1p-34f &&
                           s >= 0x1p-60f && s <= 0x1p60f;
+        // Decision-only route for supporting one-sided metrics: find the exact boundary
+        // xstar of "this rank exceeds" by probing 64 consecutive floats around
+        // med +- thr*s with the defining operations (IEEE subtract and divide).
+        bool decide = fast && !prim && dir != 0;
+        float xstar = 0.0f;
+        if (decide) {
+            const float xc = dir > 0 ? med + thr * s : med - thr * s;
+            const uint32_t kc = key_of(xc);
+            decide = kc >= 64u && kc <= 0xFF800000u - 64u;
+            if (decide) {
+                const float xl = float_of_key(kc + (uint32_t)lane - 32u);
+                const float zl = dir > 0 ? (xl - med) / s : (med - xl) / s;
+                const uint64_t mk = __ballot(zl > thr);
+                // higher is worse: lanes f..63 true; lower is worse: lanes 0..g-1 true
+                const uint64_t want = dir > 0 ? mk : ~mk;
+                const int f = want ? __builtin_ctzll(want) : 64;
+                decide = f >= 1 && f <= 63 && want == (~0ull << f);
+                if (decide) xstar = __uint_as_float((uint32_t)__builtin_amdgcn_readlane(
+                                (int)__float_as_uint(xl), dir > 0 ? f : f - 1));
+            }
+        }
         if (fast) {
             const float ss = dir < 0 ? -s : s;
             const float rs = 1.0f / ss;
+            if (decide) {
+                // |estimate - exact node score| < |cc| * (sum(x) + 8*med) * 2^-20 + |thr| * 2^-23
+                // and sum(x) + 8*med <= 16 * max(x):
+                const float cc = a.node_scale * rs;
+                const float kk = (8.0f * med) * cc;
+                const float margin = __builtin_fmaf(fabsf(cc) * __uint_as_float(umax), 0x1.01p-16f,
+                                                    fabsf(thr) * 0x1p-22f);
+                auto zdecide = [&](auto lower) {
+#pragma unroll
+                    for (int j = 0; j < ROWS; ++j) {
+                        uint32_t e;
+                        float nz;
+                        bool near;
+                        score_row_decide<decltype(lower)::value>(v[j], xstar, cc, kk, thr, margin, &e, &nz, &near);
+                        if (__ballot(near)) {       // rare: settle the row with the exact chain
+                            uint32_t e2;
+                            score_row_fast<false>(v[j], med, ss, rs, thr, a.node_scale, &e2, &nz);
+                        }
+                        __hip_atomic_fetch_or(&emask[j * NT + tz / 4], e << m, __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_WORKGROUP);
+                        NE[j / 4] |= (nz > thr ? 1u : 0u) << (8 * (j & 3) + m);
+                        asm volatile("" : "+v"(NE[j / 4]));
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                };
+                if (dir > 0) zdecide(std::false_type{});
+                else zdecide(std::true_type{});
+            } else {
             auto zfast = [&](auto two_sided) {
 #pragma unroll
                 for (int j = 0; j < ROWS; ++j) {
@@ -551,6 +627,7 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
             };
             if (dir != 0) zfast(std::false_type{});
             else zfast(std::true_type{});
+            }
         } else {
             const uint32_t absmask = dir == 0 ? 0x7FFFFFFFu : 0xFFFFFFFFu;
             const uint32_t sgnmask = dir < 0 ? 0x80000000u : 0u;

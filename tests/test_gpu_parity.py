@@ -64,6 +64,23 @@ def test_node_aggregation_rules_and_options(agg, R):
     say("  report", rep)
 
 
+@pytest.mark.parametrize("thr", [0.0, -0.75, 1e-3, 2.0, 30.0])
+def test_thresholds_that_crowd_the_decision_boundary(thr):
+    """With the threshold inside the bulk of the node scores many estimated node
+    scores fall within the rounding margin and must be settled exactly."""
+    R, M, T = 65536, 4, 3
+    say(f"case crowded threshold thr={thr}")
+    g = torch.Generator().manual_seed(17)
+    x = torch.exp(0.02 * torch.randn((T, M, R), generator=g, dtype=torch.float64))
+    x[:, 1] = 400.0 / x[:, 1]
+    x[:, :, 4096:4104] *= 1.05
+    x = x.to(torch.float32)
+    p = oracle_params(R=R, M=M, W=3, k=2, thr=thr, directions=(1, -1, 1, 0), min_signals=2)
+    rep = run_and_compare(p, x, topk_k=16, label=f"thr{thr}")
+    say("  report", rep)
+    assert rep["z_bit_exact"]
+
+
 def test_tiny_configuration():
     w = workload(0)
     say("case", w.name)
