@@ -43,10 +43,12 @@ template <int NT, int LOG_NB, int MAX_NODES>
 struct Shared {
     static constexpr int NB = 1 << LOG_NB;
     uint32_t hist[NB];
-    uint32_t cand[CAND_CAP];
+    uint32_t pref[NB + 4];     // exclusive prefix sums of hist (pref[NB] = total), for the MAD shortcut
+    uint32_t cand[CAND_CAP + 4];   // 16-byte aligned; read four at a time when ranking
     uint32_t wpart[16];
     uint32_t below, ncand;
     uint32_t smin, smax;       // extremes of the sample keys
+    uint32_t d1, d2;           // MAD shortcut: distance interval holding the wanted ranks
     uint32_t umax[2];          // largest raw bit pattern of the column (double-buffered)
     uint32_t res[6];           // ba, prefix before ba, bb, prefix through bb, va, vb
     uint8_t nodeb[MAX_NODES];
@@ -170,7 +172,7 @@ struct DKeys {
 // After a counting pass: find the buckets holding ranks ka and kb (relative to
 // everything, `below` keys lie under the histogram's range).  Results in sh.res.
 // Returns whether both ranks fall inside the histogram.  Ends with a barrier.
-template <int NT, int LOG_NB, typename SH>
+template <int NT, int LOG_NB, bool WRITE_PREF, typename SH>
 __device__ __forceinline__ bool locate(SH& sh, uint32_t tid, uint32_t ka, uint32_t kb,
                                        uint32_t* total_out) {
     constexpr int BPT = (1 << LOG_NB) / NT;
@@ -181,6 +183,12 @@ __device__ __forceinline__ bool locate(SH& sh, uint32_t tid, uint32_t ka, uint32
     const uint32_t excl = block_excl_scan<NT>(s, tid, sh.wpart, &total);
     const uint32_t below = sh.below;
     const uint32_t ra = ka - below, rb = kb - below;   // wrap when not bracketed
+    if (WRITE_PREF) {
+        uint32_t p = excl;
+#pragma unroll
+        for (int q = 0; q < BPT; ++q) { sh.pref[tid * BPT + q] = p; p += loc[q]; }
+        if (tid == NT - 1) sh.pref[1 << LOG_NB] = p;
+    }
     if (ra - excl < s) {
         uint32_t p = excl;
         bool done = false;
@@ -204,6 +212,30 @@ __device__ __forceinline__ bool locate(SH& sh, uint32_t tid, uint32_t ka, uint32
     return rfl(ka >= below && rb < total) != 0;
 }
 
+// Exact ranking of the cnt gathered candidates in sh.cand (ties broken by
+// position): the candidates of rank wa and wb go to sh.res[4] and sh.res[5].
+// Each wave takes every (NT/64)-th candidate; its lanes split the comparisons
+// and add their counts up across the wave.  Ends with a barrier.
+template <int NT, typename SH>
+__device__ __forceinline__ void rank_candidates(SH& sh, uint32_t tid, uint32_t cnt, uint32_t wa,
+                                                uint32_t wb) {
+    const uint32_t lane = tid & (WAVE - 1), w = rfl(tid >> 6);
+    for (uint32_t i = w; i < cnt; i += NT / WAVE) {
+        const uint32_t c = sh.cand[i];
+        uint32_t r = 0;
+        for (uint32_t j = lane; j < cnt; j += WAVE) {
+            const uint32_t cj = sh.cand[j];
+            r += (cj < c || (cj == c && j < i)) ? 1u : 0u;
+        }
+        r = wave_incl_scan(r);
+        if (lane == WAVE - 1) {
+            if (r == wa) sh.res[4] = c;
+            if (r == wb) sh.res[5] = c;
+        }
+    }
+    __syncthreads();
+}
+
 template <int LOG_NB>
 __device__ __forceinline__ int shift_for(uint32_t span) {
     const int width = 32 - __builtin_clz(span | 1u);
@@ -222,10 +254,17 @@ __device__ __forceinline__ int shift_for(uint32_t span) {
 //      over the full range.
 //   3. The buckets holding the ranks are gathered into LDS and ranked exactly,
 //      or, when they are crowded (ties), the range is narrowed to the bucket.
-template <int NT, int ROWS, int LOG_NB, typename SH, typename Keys>
-__device__ __forceinline__ void block_select(SH& sh, const Keys& keys, uint32_t skey, bool svalid,
+//
+// WIDE: bracket the sample ranks n/2 -+ 0.34*n instead, so that the histogram also
+// covers the values around median -+ MAD, and keep its prefix sums in sh.pref.  If
+// the first counting pass settles the selection, *hist_lo / *hist_shift describe
+// that histogram (bucket b holds keys hist_lo + b*2^shift ...) and the function
+// returns true; the MAD shortcut then reads the prefix sums.
+template <int NT, int ROWS, int LOG_NB, bool WIDE, typename SH, typename Keys>
+__device__ __forceinline__ bool block_select(SH& sh, const Keys& keys, uint32_t skey, bool svalid,
                                              uint32_t n, uint32_t k0, uint32_t k1, uint32_t* out0,
-                                             uint32_t* out1) {
+                                             uint32_t* out1, uint32_t* hist_lo = nullptr,
+                                             uint32_t* hist_hi = nullptr, int* hist_shift = nullptr) {
     constexpr int NB = 1 << LOG_NB;
     constexpr int BPT = NB / NT;
     static_assert(BPT >= 1 && (BPT % 4 == 0 || BPT < 4), "bucket split");
@@ -247,21 +286,22 @@ __device__ __forceinline__ void block_select(SH& sh, const Keys& keys, uint32_t 
         if (svalid) atomicAdd(&sh.hist[(skey - smin) >> sshift], 1u);
         __syncthreads();
         // n valid samples: the ranks n/2 -+ (2*sqrt(n) + 1) bracket the column's median
-        const uint32_t delta = (uint32_t)(2.0f * __builtin_sqrtf((float)n)) + 1u;
+        const uint32_t delta = WIDE ? (n * 87u) >> 8 : (uint32_t)(2.0f * __builtin_sqrtf((float)n)) + 1u;
         const uint32_t half = n / 2;
         const uint32_t ra = half > delta ? half - 1 - delta : 0u;
         const uint32_t rb = min(n - 1, half + delta);
         uint32_t tot;
-        (void)locate<NT, LOG_NB>(sh, tid, ra, rb, &tot);
+        (void)locate<NT, LOG_NB, false>(sh, tid, ra, rb, &tot);
         const uint32_t ba = rfl(sh.res[0]), bb = rfl(sh.res[2]);
         lo = ra == 0 ? 0u : smin + (ba << sshift);
         const uint64_t hend = (uint64_t)smin + ((uint64_t)(bb + 1) << sshift) - 1;
         hi = rb == n - 1 ? 0xFFFFFFFFu : (hend > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)hend);
     }
     // mode 0: both statistics together; 1: k0 alone; 2: k1 alone (after a split)
-    int mode = 0;
+    int mode = 0, rounds = 0;
     uint32_t ka = k0, kb = k1, v0 = 0, v1 = 0;
     for (;;) {
+        ++rounds;
         const uint32_t span = hi - lo;
         const int shift = shift_for<LOG_NB>(span);
         // a fresh copy of the thread index per round: values derived from it (bucket
@@ -294,7 +334,7 @@ __device__ __forceinline__ void block_select(SH& sh, const Keys& keys, uint32_t 
         if (lane == WAVE - 1 && nbelow) atomicAdd(&sh.below, nbelow);
         __syncthreads();
         uint32_t total;
-        const bool bracketed = locate<NT, LOG_NB>(sh, tid, ka, kb, &total);
+        const bool bracketed = locate<NT, LOG_NB, WIDE>(sh, tid, ka, kb, &total);
         if (!bracketed) {               // the bracket missed: count over all keys
             lo = 0; hi = 0xFFFFFFFFu;
             continue;
@@ -327,17 +367,7 @@ __device__ __forceinline__ void block_select(SH& sh, const Keys& keys, uint32_t 
             __syncthreads();
             const uint32_t cnt = min(sh.ncand, (uint32_t)CAND_CAP);
             const uint32_t wa = ka - below - pa, wb = kb - below - pa;
-            for (uint32_t i = tid; i < cnt; i += NT) {
-                const uint32_t c = sh.cand[i];
-                uint32_t r = 0;
-                for (uint32_t j = 0; j < cnt; ++j) {
-                    const uint32_t cj = sh.cand[j];
-                    r += (cj < c || (cj == c && j < i)) ? 1u : 0u;
-                }
-                if (r == wa) sh.res[4] = c;
-                if (r == wb) sh.res[5] = c;
-            }
-            __syncthreads();
+            rank_candidates<NT>(sh, tid, cnt, wa, wb);
             va = rfl(sh.res[4]); vb = rfl(sh.res[5]);
         } else {
             // crowded (ties): look inside bucket ba; if the two statistics sit in
@@ -349,13 +379,119 @@ __device__ __forceinline__ void block_select(SH& sh, const Keys& keys, uint32_t 
             lo = nlo;
             continue;
         }
-        if (mode == 0) { v0 = va; v1 = vb; break; }
+        if (mode == 0) {
+            v0 = va; v1 = vb;
+            if (WIDE && hist_lo) { *hist_lo = lo; *hist_hi = hi; *hist_shift = shift; }
+            break;
+        }
         if (mode == 1) { v0 = va; mode = 2; ka = kb = k1; lo = 0; hi = 0xFFFFFFFFu; continue; }
         v1 = va;
         break;
     }
     *out0 = v0;
     *out1 = v1;
+    return rounds == 1 && mode == 0;
+}
+
+// MAD shortcut for a sign-free column whose median selection left a histogram of
+// the raw bits over [lo, hi] (2^shift keys per bucket, prefix sums in sh.pref)
+// that reaches well beyond median -+ MAD.  From the prefix sums alone the threads
+// find a distance interval [d1, d2] that must hold the wanted order statistics of
+// |x - med| (see below); one pass then counts the distances below d1 exactly and
+// gathers those inside the interval (a few dozen) for exact ranking.  The pass
+// also verifies the interval; false is returned, and the caller selects in the
+// ordinary way, if the histogram did not reach far enough or the check fails.
+template <int NT, int ROWS, int LOG_NB, typename SH>
+__device__ __forceinline__ bool mad_from_histogram(SH& sh, const float (&v)[ROWS][4], float med,
+                                                   uint32_t lo, uint32_t hi, int shift, uint32_t k0,
+                                                   uint32_t k1, uint32_t* out0, uint32_t* out1) {
+    constexpr int NB = 1 << LOG_NB;
+    const uint32_t tid = opaque_v(threadIdx.x), lane = tid & (WAVE - 1);
+    const float xlo = __uint_as_float(lo), xhi = __uint_as_float(hi);
+    const float dmax = fminf(med - xlo, xhi - med);
+    if (!(dmax > 0.0f) || shift < 2) return false;
+    if (tid == 0) { sh.d1 = 0; sh.d2 = 0xFFFFFFFFu; sh.ncand = 0; sh.below = 0; }
+    __syncthreads();
+    {
+        // Pairs of bucket edges (eL, eR) with value(eL) <= med < value(eR): the set
+        // S = {eL <= key < eR} is counted exactly by the prefix sums, every value
+        // outside S is at least min(dL, dR) away from med and every value inside at
+        // most max(dL, dR) (subtraction is monotone), where dL = med - value(eL) and
+        // dR = value(eR) - med.  So |S| <= k0 makes min(dL, dR) a valid d1 and
+        // |S| >= k1 + 1 makes max(dL, dR) a valid d2.  Each thread pairs its own
+        // buckets' edges with the two edges that nearly mirror them.
+        constexpr int BPT = NB / NT;
+        uint32_t c1 = 0, c2 = 0xFFFFFFFFu;
+        auto edge = [&](uint32_t b) { return __uint_as_float(lo + (b << shift)); };
+        const uint32_t bmax = (hi - lo) >> shift;     // last bucket whose lower edge is <= hi
+        auto eval = [&](uint32_t bL, uint32_t bR) {
+            if (bL < bR && bR <= bmax) {
+                const float xl = edge(bL), xr = edge(bR);
+                if (xl <= med && xr > med) {
+                    const float dl = med - xl, dr = xr - med;
+                    const uint32_t cntS = sh.pref[bR] - sh.pref[bL];
+                    if (cntS <= k0) c1 = max(c1, __float_as_uint(fminf(dl, dr)));
+                    if (cntS >= k1 + 1) c2 = min(c2, __float_as_uint(fmaxf(dl, dr)));
+                }
+            }
+        };
+#pragma unroll
+        for (int q = 0; q < BPT; ++q) {
+            const uint32_t b = tid * BPT + q;
+            const float xe = edge(b);
+            if (xe > med) {            // a right edge: mirror it to the left
+                const uint32_t km = __float_as_uint(med - (xe - med));
+                if (km >= lo && km <= hi) {
+                    const uint32_t bl = (km - lo) >> shift;
+                    eval(bl, b);
+                    eval(bl + 1, b);
+                }
+            } else {                   // a left edge: mirror it to the right
+                const uint32_t km = __float_as_uint(med + (med - xe));
+                if (km >= lo && km <= hi) {
+                    const uint32_t br = (km - lo) >> shift;
+                    eval(b, br);
+                    eval(b, br + 1);
+                }
+            }
+        }
+        c1 = wave_max_to_last(c1);
+        c2 = wave_min_to_last(c2);
+        if (lane == WAVE - 1) { atomicMax(&sh.d1, c1); atomicMin(&sh.d2, c2); }
+    }
+    __syncthreads();
+    const uint32_t d1 = rfl(sh.d1), d2 = rfl(sh.d2);
+    if (d2 == 0xFFFFFFFFu || d2 < d1) return false;
+    // exact pass: count |x - med| below d1, gather those in [d1, d2]
+    const uint32_t span = d2 - d1;
+    uint32_t nbelow = 0;
+    {
+        const uint32_t tok = opaque_s(__float_as_uint(med));
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t kk = __float_as_uint(fabsf(v[j][i] - __uint_as_float(tok)));
+                nbelow += kk < d1 ? 1u : 0u;
+                if (kk - d1 <= span) {
+                    uint32_t pos = atomicAdd(&sh.ncand, 1u);
+                    if (pos < (uint32_t)CAND_CAP) sh.cand[pos] = kk;
+                }
+            }
+            asm volatile("" : "+v"(nbelow));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    nbelow = wave_incl_scan(nbelow);
+    if (lane == WAVE - 1 && nbelow) atomicAdd(&sh.below, nbelow);
+    __syncthreads();
+    const uint32_t below = rfl(sh.below), cnt = rfl(sh.ncand);
+    if (cnt > (uint32_t)CAND_CAP || below > k0 || k1 >= below + cnt) return false;
+    const uint32_t wa = k0 - below, wb = k1 - below;
+    rank_candidates<NT>(sh, tid, cnt, wa, wb);
+    *out0 = rfl(sh.res[4]);
+    *out1 = rfl(sh.res[5]);
+    return true;
 }
 
 // Signed score and node score of one register row, dividing with the IEEE
@@ -528,17 +664,25 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
 
         uint32_t s0, s1;
         float med;
+        bool have_mad = false;
         if (!signs) {
-            block_select<NT, ROWS, LOG_NB>(sh, XKeys<ROWS, true>{v}, __float_as_uint(v[0][0]), svalid,
-                                           nsample, k0, k1, &s0, &s1);
+            uint32_t hlo = 0, hhi = 0;
+            int hshift = 0;
+            const bool one_round = block_select<NT, ROWS, LOG_NB, true>(
+                sh, XKeys<ROWS, true>{v}, __float_as_uint(v[0][0]), svalid, nsample, k0, k1, &s0, &s1,
+                &hlo, &hhi, &hshift);
             med = 0.5f * (__uint_as_float(s0) + __uint_as_float(s1));
+            if (one_round)
+                have_mad = mad_from_histogram<NT, ROWS, LOG_NB>(sh, v, med, hlo, hhi, hshift, k0, k1, &s0, &s1);
         } else {
-            block_select<NT, ROWS, LOG_NB>(sh, XKeys<ROWS, false>{v}, key_of(v[0][0] + 0.0f), svalid,
-                                           nsample, k0, k1, &s0, &s1);
+            block_select<NT, ROWS, LOG_NB, false>(sh, XKeys<ROWS, false>{v}, key_of(v[0][0] + 0.0f),
+                                                  svalid, nsample, k0, k1, &s0, &s1);
             med = 0.5f * (float_of_key(s0) + float_of_key(s1));
         }
-        block_select<NT, ROWS, LOG_NB>(sh, DKeys<ROWS>{v, med}, __float_as_uint(fabsf(v[0][0] - med)),
-                                       svalid, nsample, k0, k1, &s0, &s1);
+        if (!have_mad)
+            block_select<NT, ROWS, LOG_NB, false>(sh, DKeys<ROWS>{v, med},
+                                                  __float_as_uint(fabsf(v[0][0] - med)), svalid, nsample,
+                                                  k0, k1, &s0, &s1);
         const float mad = 0.5f * (__uint_as_float(s0) + __uint_as_float(s1));
         if (tid == 0) {
             a.med[t * M + m] = med;
