@@ -597,9 +597,14 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
     const int tid = threadIdx.x, lane = tid & (WAVE - 1);
     const int w = rfl(tid >> 6);
     const uint32_t R = a.R, N = a.N, M = a.M;
-    const size_t t = blockIdx.x;
     const uint32_t RW = (R + 63) / 64, NWD = (N + 63) / 64;
     const float thr = a.thr;
+    // Each workgroup scores a contiguous run of steps, column after column, and
+    // loads the next column while it scores the current one.
+    const uint32_t spw = (a.T + gridDim.x - 1) / gridDim.x;
+    const uint32_t t_begin = blockIdx.x * spw;
+    const uint32_t t_end = min(a.T, t_begin + spw);
+    if (t_begin >= t_end) return;
 
     // Row j of wave w covers rank block (j + w) % ROWS, so that the first
     // registers to arrive (row 0) sample the whole rank range.
@@ -612,10 +617,6 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
     auto fresh_tid4 = [&]() -> uint32_t { return opaque_v((uint32_t)tid * 4); };
 
     uint32_t NE[(ROWS + 3) / 4]; // node mask byte per row, packed
-#pragma unroll
-    for (int j = 0; j < ROWS; ++j) emask[j * NT + tid] = 0;   // each slot is private to its thread
-#pragma unroll
-    for (int j = 0; j < (ROWS + 3) / 4; ++j) NE[j] = 0;
     if (tid == 0) { sh.umax[0] = 0; sh.umax[1] = 0; sh.ncand = 0; }
     __syncthreads();
     // number of threads whose sampled element (row 0) is a real rank
@@ -629,21 +630,38 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
 
     const uint32_t k0 = R / 2 - 1, k1 = R / 2;   // R is even
 
-    for (uint32_t m = 0; m < M; ++m) {
-        const float* col = a.x + (t * M + m) * (size_t)R;
-        float v[ROWS][4];
-        const uint32_t tl = fresh_tid4();
-#pragma unroll
-        for (int j = 0; j < ROWS; ++j) {
-            float4 q;
-            if (FULL || rbase(j, tl) < R) {
-                q = *reinterpret_cast<const float4*>(col + rbase(j, tl));
-            } else {   // padding: a NaN, whose key lies above every real key
-                const float pad = __uint_as_float(0x7FFFFFFFu);
-                q = make_float4(pad, pad, pad, pad);
-            }
-            v[j][0] = q.x; v[j][1] = q.y; v[j][2] = q.z; v[j][3] = q.w;
+    float v[ROWS][4];
+    // Issue the loads of one register row of a column (padding: a NaN, whose key
+    // lies above every real key).
+    auto load_row = [&](int j, const float* col, uint32_t tid4) {
+        float4 q;
+        if (FULL || rbase(j, tid4) < R) {
+            q = *reinterpret_cast<const float4*>(col + rbase(j, tid4));
+        } else {
+            const float pad = __uint_as_float(0x7FFFFFFFu);
+            q = make_float4(pad, pad, pad, pad);
         }
+        v[j][0] = q.x; v[j][1] = q.y; v[j][2] = q.z; v[j][3] = q.w;
+    };
+    {
+        const uint32_t tl = fresh_tid4();
+        const float* col = a.x + (size_t)t_begin * M * R;
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) load_row(j, col, tl);
+    }
+
+    for (size_t t = t_begin; t < t_end; ++t) {
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) emask[j * NT + tid] = 0;   // each slot is private to its thread
+#pragma unroll
+    for (int j = 0; j < (ROWS + 3) / 4; ++j) NE[j] = 0;
+    for (uint32_t m = 0; m < M; ++m) {
+        // the column after this one (next metric, or the next step's first metric)
+        // (after the very last column the current one is simply read again: a
+        // branch-free refill keeps the register allocation of the score loops simple)
+        const bool have_next = m + 1 < M || t + 1 < t_end;
+        const float* next_col = a.x + (t * M + m + (have_next ? 1 : 0)) * (size_t)R;
+        const uint32_t tl = fresh_tid4();
         const bool svalid = FULL || rbase(0, tl) < R;
         // Largest raw bit pattern of the column: >= 0x80000000 iff some value carries
         // a sign bit (negative or -0); otherwise it is the bit pattern of the maximum.
@@ -702,6 +720,19 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
         // non-zero |x - med| lies in [2^-59, 2^59]).
         const bool fast = !signs && a.node_agg == 0 && umax <= 0x5D000000u && med >= 0x1p-34f &&
                           s >= 0x1p-60f && s <= 0x1p60f;
+        if (a.z) {   // optional full z output, recomputed so that the loops below stay lean
+                     // (it must come first: they refill the registers with the next column)
+            float* zcol = a.z + (t * M + m) * (size_t)R;
+#pragma unroll
+            for (int j = 0; j < ROWS; ++j) {
+                if (FULL || rbase(j, tz) < R) {
+                    float4 q;
+                    q.x = ((v[j][0] + 0.0f) - med) / s; q.y = ((v[j][1] + 0.0f) - med) / s;
+                    q.z = ((v[j][2] + 0.0f) - med) / s; q.w = ((v[j][3] + 0.0f) - med) / s;
+                    *reinterpret_cast<float4*>(zcol + rbase(j, tz)) = q;
+                }
+            }
+        }
         // Decision-only route for supporting one-sided metrics: find the exact boundary
         // xstar of "this rank exceeds" by probing 64 consecutive floats around
         // med +- thr*s with the defining operations (IEEE subtract and divide).
@@ -723,86 +754,55 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
                                 (int)__float_as_uint(xl), dir > 0 ? f : f - 1));
             }
         }
-        if (fast) {
-            const float ss = dir < 0 ? -s : s;
-            const float rs = 1.0f / ss;
-            if (decide) {
-                // |estimate - exact node score| < |cc| * (sum(x) + 8*med) * 2^-20 + |thr| * 2^-23
-                // and sum(x) + 8*med <= 16 * max(x):
-                const float cc = a.node_scale * rs;
-                const float kk = (8.0f * med) * cc;
-                const float margin = __builtin_fmaf(fabsf(cc) * __uint_as_float(umax), 0x1.01p-16f,
-                                                    fabsf(thr) * 0x1p-22f);
-                auto zdecide = [&](auto lower) {
+        // One loop over the register rows; the route is the same for the whole column,
+        // but it is chosen per row from an optimiser-opaque copy so that the loop is
+        // not split into one copy per route (each copy would refill the registers on
+        // its own and the column would end up held twice).
+        const float ss = dir < 0 ? -s : s;
+        const float rs = 1.0f / ss;
+        // decision-only route:
+        // |estimate - exact node score| < |cc| * (sum(x) + 8*med) * 2^-20 + |thr| * 2^-23
+        // and sum(x) + 8*med <= 16 * max(x):
+        const float cc = a.node_scale * rs;
+        const float kk = (8.0f * med) * cc;
+        const float margin = __builtin_fmaf(fabsf(cc) * __uint_as_float(umax), 0x1.01p-16f,
+                                            fabsf(thr) * 0x1p-22f);
+        const uint32_t absmask = dir == 0 ? 0x7FFFFFFFu : 0xFFFFFFFFu;
+        const uint32_t sgnmask = dir < 0 ? 0x80000000u : 0u;
+        // 0/1 decision-only (higher / lower is worse), 2/3 exact by reciprocal
+        // (one- / two-sided), 4/5 IEEE division (scaled sum / max)
+        const uint32_t route = fast ? (decide ? (dir > 0 ? 0u : 1u) : (dir != 0 ? 2u : 3u))
+                                    : (a.node_agg == 0 ? 4u : 5u);
 #pragma unroll
-                    for (int j = 0; j < ROWS; ++j) {
-                        uint32_t e;
-                        float nz;
-                        bool near;
-                        score_row_decide<decltype(lower)::value>(v[j], xstar, cc, kk, thr, margin, &e, &nz, &near);
-                        if (__ballot(near)) {       // rare: settle the row with the exact chain
-                            uint32_t e2;
-                            score_row_fast<false>(v[j], med, ss, rs, thr, a.node_scale, &e2, &nz);
-                        }
-                        __hip_atomic_fetch_or(&emask[j * NT + tz / 4], e << m, __ATOMIC_RELAXED,
-                                              __HIP_MEMORY_SCOPE_WORKGROUP);
-                        NE[j / 4] |= (nz > thr ? 1u : 0u) << (8 * (j & 3) + m);
-                        asm volatile("" : "+v"(NE[j / 4]));
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                };
-                if (dir > 0) zdecide(std::false_type{});
-                else zdecide(std::true_type{});
+        for (int j = 0; j < ROWS; ++j) {
+            const uint32_t rt = opaque_s(route);
+            uint32_t e;
+            float nz;
+            if (rt <= 1u) {
+                bool near;
+                if (rt == 0u) score_row_decide<false>(v[j], xstar, cc, kk, thr, margin, &e, &nz, &near);
+                else score_row_decide<true>(v[j], xstar, cc, kk, thr, margin, &e, &nz, &near);
+                if (__ballot(near)) {       // rare: settle the row with the exact chain
+                    uint32_t e2;
+                    score_row_fast<false>(v[j], med, ss, rs, thr, a.node_scale, &e2, &nz);
+                }
+            } else if (rt == 2u) {
+                score_row_fast<false>(v[j], med, ss, rs, thr, a.node_scale, &e, &nz);
+            } else if (rt == 3u) {
+                score_row_fast<true>(v[j], med, ss, rs, thr, a.node_scale, &e, &nz);
+            } else if (rt == 4u) {
+                score_row<0>(v[j], med, s, absmask, sgnmask, thr, a.node_scale, &e, &nz);
             } else {
-            auto zfast = [&](auto two_sided) {
-#pragma unroll
-                for (int j = 0; j < ROWS; ++j) {
-                    uint32_t e;
-                    float nz;
-                    score_row_fast<decltype(two_sided)::value>(v[j], med, ss, rs, thr, a.node_scale, &e, &nz);
-                    __hip_atomic_fetch_or(&emask[j * NT + tz / 4], e << m, __ATOMIC_RELAXED,
-                                          __HIP_MEMORY_SCOPE_WORKGROUP);
-                    NE[j / 4] |= (nz > thr ? 1u : 0u) << (8 * (j & 3) + m);
-                    if (prim && (FULL || rbase(j, tz) < R) && !(tz & 4)) nzrow[rbase(j, tz) / 8] = nz;
-                    // pin the row's results here, or its scores stay live until the loop ends
-                    asm volatile("" : "+v"(NE[j / 4]));
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            };
-            if (dir != 0) zfast(std::false_type{});
-            else zfast(std::true_type{});
+                score_row<1>(v[j], med, s, absmask, sgnmask, thr, a.node_scale, &e, &nz);
             }
-        } else {
-            const uint32_t absmask = dir == 0 ? 0x7FFFFFFFu : 0xFFFFFFFFu;
-            const uint32_t sgnmask = dir < 0 ? 0x80000000u : 0u;
-            auto zphase = [&](auto agg) {
-#pragma unroll
-                for (int j = 0; j < ROWS; ++j) {
-                    uint32_t e;
-                    float nz;
-                    score_row<decltype(agg)::value>(v[j], med, s, absmask, sgnmask, thr, a.node_scale, &e, &nz);
-                    __hip_atomic_fetch_or(&emask[j * NT + tz / 4], e << m, __ATOMIC_RELAXED,
-                                          __HIP_MEMORY_SCOPE_WORKGROUP);
-                    NE[j / 4] |= (nz > thr ? 1u : 0u) << (8 * (j & 3) + m);
-                    if (prim && (FULL || rbase(j, tz) < R) && !(tz & 4)) nzrow[rbase(j, tz) / 8] = nz;
-                    asm volatile("" : "+v"(NE[j / 4]));
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            };
-            if (a.node_agg == 0) zphase(std::integral_constant<int, 0>{});
-            else zphase(std::integral_constant<int, 1>{});
-        }
-        if (a.z) {   // optional full z output, recomputed so that the loops above stay lean
-            float* zcol = a.z + (t * M + m) * (size_t)R;
-#pragma unroll
-            for (int j = 0; j < ROWS; ++j) {
-                if (FULL || rbase(j, tz) < R) {
-                    float4 q;
-                    q.x = ((v[j][0] + 0.0f) - med) / s; q.y = ((v[j][1] + 0.0f) - med) / s;
-                    q.z = ((v[j][2] + 0.0f) - med) / s; q.w = ((v[j][3] + 0.0f) - med) / s;
-                    *reinterpret_cast<float4*>(zcol + rbase(j, tz)) = q;
-                }
-            }
+            __hip_atomic_fetch_or(&emask[j * NT + tz / 4], e << m, __ATOMIC_RELAXED,
+                                  __HIP_MEMORY_SCOPE_WORKGROUP);
+            NE[j / 4] |= (nz > thr ? 1u : 0u) << (8 * (j & 3) + m);
+            if (prim && (FULL || rbase(j, tz) < R) && !(tz & 4)) nzrow[rbase(j, tz) / 8] = nz;
+            load_row(j, next_col, tz);      // the row is done: refill it with the next column
+            // pin the row's results here, or its scores stay live until the loop ends
+            asm volatile("" : "+v"(NE[j / 4]));
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 
@@ -846,6 +846,7 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
         const uint64_t word = __ballot(an);
         if (lane == 0) a.node_anom[t * NWD + wd] = word;
     }
+    }   // steps of this workgroup
 }
 
 template <int NT, int ROWS, int LOG_NB, bool FULL>
@@ -861,7 +862,21 @@ hipError_t launch_one(const gd_score_args& a, hipStream_t s) {
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL(kern, dim3(a.T), dim3(NT), lds, s, a);
+    // Enough workgroups to fill every CU once (as many as fit by LDS and wave
+    // slots); each takes a contiguous run of ceil(T / grid) steps.
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        if (n_cu <= 0) n_cu = 256;
+    }
+    const size_t by_lds = (size_t)160 * 1024 / lds, by_waves = (size_t)16 / (NT / WAVE);
+    const size_t per_cu = by_lds < by_waves ? (by_lds ? by_lds : 1) : by_waves;
+    const size_t cap = (size_t)n_cu * per_cu;
+    const uint32_t grid = (uint32_t)(a.T < cap ? a.T : cap);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, s, a);
     return hipGetLastError();
 }
 
