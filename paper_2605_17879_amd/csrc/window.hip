@@ -7,24 +7,21 @@
 // count of set bits inside the window; the first flagged step (+1, 0 = never).
 //
 // One thread owns one item and one wave owns one 64-item word column of the
-// ring, so every ring word is read and written by a single wave.  A wave loads
-// 64 steps' words at a time (lane l takes step s0 + l) and walks them through
-// lane broadcasts; the bit leaving the window at step t is the bit that entered
-// at t - W, taken from the batch itself when it is recent enough, else from the
-// ring.
+// ring, so every ring word is read and written by a single wave.  A wave takes
+// 64 steps at a time: lane l fetches the word entering at step s0 + l and the
+// word leaving the window at that step (the one that entered W steps earlier,
+// from the batch itself when recent enough, else from the ring).  Two 64x64 bit
+// transposes across the lanes turn them into per-item time vectors, so a block
+// of 64 steps updates the count with two popcounts.  Only an item that could
+// reach k inside the block (count + entering bits >= k, not flagged before)
+// walks the block step by step to find its first flagged step.
 #include "gd_internal.h"
+#include "gd_lanes.h"
 
 namespace {
 
 constexpr int WAVE = 64;
 constexpr int WIN_NT = 256;
-
-// Value of lane l (uniform over the wave) of a 64-bit register.
-__device__ __forceinline__ uint64_t bcast64(uint64_t v, uint32_t l) {
-    const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)v, (int)l);
-    const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), (int)l);
-    return ((uint64_t)hi << 32) | lo;
-}
 
 // Items [0, R) are ranks, then, starting at a fresh workgroup, items [0, N) are nodes.
 __global__ __launch_bounds__(WIN_NT) void window_kernel(const gd_window_args a) {
@@ -33,7 +30,7 @@ __global__ __launch_bounds__(WIN_NT) void window_kernel(const gd_window_args a) 
     const uint32_t n_items = is_node ? a.N : a.R;
     const uint32_t blk = is_node ? blockIdx.x - rank_blocks : blockIdx.x;
     const uint32_t item = blk * WIN_NT + threadIdx.x;
-    const int lane = threadIdx.x & (WAVE - 1);
+    const uint32_t lane = threadIdx.x & (WAVE - 1);
     const uint32_t words = (n_items + 63) / 64;
     const uint32_t word = item / 64;                 // uniform over the wave
     if (word >= words) return;                       // whole wave out of range
@@ -44,26 +41,41 @@ __global__ __launch_bounds__(WIN_NT) void window_kernel(const gd_window_args a) 
     const bool live = item < n_items;
     const uint32_t W = a.W, K = a.K, T = a.T;
 
+    // the entering and the leaving word of step s (lane l of a block asks for s0 + l)
+    auto fetch = [&](uint32_t s, uint64_t* win, uint64_t* wout) {
+        *win = 0; *wout = 0;
+        if (s < T) {
+            *win = anom[(size_t)s * words + word];
+            const uint64_t t = a.first_step + s;
+            if (t >= W)
+                *wout = s >= W ? anom[(size_t)(s - W) * words + word]
+                               : ring[(size_t)(t % W) * words + word];
+        }
+    };
+
     uint32_t c = live ? count[item] : 0;
     int32_t f = live ? first[item] : 0;
+    uint64_t win, wout;
+    fetch(lane, &win, &wout);
     for (uint32_t s0 = 0; s0 < T; s0 += WAVE) {
-        // lane l fetches the entering and the leaving word of step s0 + l
-        const uint32_t s = s0 + lane;
-        uint64_t win = 0, wout = 0;
-        if (s < T) {
-            win = anom[(size_t)s * words + word];
-            const uint64_t t = a.first_step + s;
-            if (t >= W) {
-                wout = s >= W ? anom[(size_t)(s - W) * words + word]
-                              : ring[(size_t)(t % W) * words + word];
+        uint64_t win_n, wout_n;                       // the next block is fetched ahead
+        fetch(s0 + WAVE + lane, &win_n, &wout_n);
+        // bit j of `in` / `out`: does this item enter / leave as anomalous at step s0 + j
+        const uint64_t in = gd_transpose64(win, lane);
+        const uint64_t out = gd_transpose64(wout, lane);
+        const uint32_t pin = __popcll(in), pout = __popcll(out);
+        if (f == 0 && c + pin >= K) {                 // the flag may first rise inside this block
+            const uint32_t n = min((uint32_t)WAVE, T - s0);
+            for (uint32_t j = 0; j < n; ++j) {
+                const uint64_t upto = (2ull << j) - 1;
+                if (c + __popcll(in & upto) - __popcll(out & upto) >= K) {
+                    f = (int32_t)(a.first_step + s0 + j) + 1;
+                    break;
+                }
             }
         }
-        const uint32_t cnt = min((uint32_t)WAVE, T - s0);
-        for (uint32_t l = 0; l < cnt; ++l) {
-            const uint64_t wi = bcast64(win, l), wo = bcast64(wout, l);
-            c += (uint32_t)((wi >> lane) & 1u) - (uint32_t)((wo >> lane) & 1u);
-            if (c >= K && f == 0) f = (int32_t)(a.first_step + s0 + l) + 1;
-        }
+        c += pin - pout;
+        win = win_n; wout = wout_n;
     }
     if (live) {
         count[item] = (uint16_t)c;
