@@ -194,3 +194,53 @@ def test_device_division_is_correctly_rounded():
     rep = compare_scores(o, gpu, "division")
     assert rep["z_bit_exact"]
     det.close()
+
+
+def _full_size_case(w, seed, chunk, min_flagged_nodes):
+    """Score the whole workload in ONE gd_score_batch call on GPU-generated data,
+    then window / flags / top-k.  The oracle scores every step of the same bytes
+    (chunk by chunk through host memory) and every output is compared bit for
+    bit; its own anomaly words feed its persistence run over the full history."""
+    x = generate(w, seed=seed, device="cuda")
+    p = oracle_params(w)
+    det = detector_for(p)
+    out = det.alloc_outputs(w.T, want_z=False)
+    det.score_batch(x, out)
+    det.update_window(out, w.T)
+    torch.cuda.synchronize()
+    ra, na, near = [], [], [0, 0]
+    last_node_z = None
+    for t0 in range(0, w.T, chunk):
+        t1 = min(w.T, t0 + chunk)
+        o = oracle.score(p, x[t0:t1].cpu().numpy(), want_z=False)
+        g = {k: (v[t0:t1] if v is not None else None) for k, v in out.items()}
+        compare_scores(o, g, f"steps [{t0},{t1})")
+        ra.append(o.rank_anom); na.append(o.node_anom)
+        near[0] += o.near_rank; near[1] += o.near_node
+        last_node_z = o.node_z[-1]
+        say(f"  steps [{t0},{t1}) match")
+    del x
+    pr = oracle.window(p.R, np.concatenate(ra), p.W, p.k)
+    pn = oracle.window(p.N, np.concatenate(na), p.W, p.k)
+    d = dict(ranks=pr, nodes=pn, node_flag_byte=oracle.node_flag_byte(p.G, pn.flag, pr.flag))
+    d["topk_idx"], d["topk_key"] = oracle.topk(pn.count, last_node_z, w.topk)
+    compare_decision(p, d, det, w.topk, label="full-size decision")
+    say("  near-threshold comparisons (rank, node):", near, "flagged ranks", int(pr.flag.sum()),
+        "flagged nodes", int(pn.flag.sum()))
+    assert int(pn.flag.sum()) >= min_flagged_nodes
+    det.close()
+
+
+def test_bench_workload_at_full_size():
+    """The benchmark's own launch configuration: 65 536 ranks x 4 096 steps x 8 metrics
+    (8 GiB) in one call."""
+    w = workload(3)
+    say("case full-size bench workload", w.name)
+    _full_size_case(w, seed=3, chunk=256, min_flagged_nodes=20)   # 32 nodes drift to +20%
+
+
+def test_configuration_2_at_full_size():
+    """16 384 ranks x 10 000 steps x 4 metrics (2.6 GB) in one call."""
+    w = workload(2)
+    say("case full-size", w.name)
+    _full_size_case(w, seed=2, chunk=1000, min_flagged_nodes=30)  # 64 grey nodes, 3-20% slow
