@@ -51,6 +51,10 @@ struct Shared {
     uint32_t d1, d2;           // MAD shortcut: distance interval holding the wanted ranks
     uint32_t umax[2];          // largest raw bit pattern of the column (double-buffered)
     uint32_t res[6];           // ba, prefix before ba, bb, prefix through bb, va, vb
+    // Per metric, from the previous step scored by this workgroup: the median and how
+    // far below / above it the counting histogram reached (hok = the hint is usable).
+    float hmed[8], hwl[8], hwh[8];
+    uint32_t hok[8];
     uint8_t nodeb[MAX_NODES];
 };
 
@@ -169,19 +173,29 @@ struct DKeys {
     __device__ __forceinline__ float value(uint32_t k) const { return __uint_as_float(k); }
 };
 
+// LDS protocol of the selection code.  Between uses the work area is kept in a
+// known state, so that no phase has to clear it behind two barriers of its own:
+// sh.hist all zero (locate() clears what it reads), sh.below = sh.ncand = 0,
+// sh.smin = ~0, sh.smax = 0, sh.d1 = 0, sh.d2 = ~0.  Thread 0 restores a scalar
+// after the barrier that follows its last read, and at least one more barrier
+// precedes the next atomic update of it.
+
 // After a counting pass: find the buckets holding ranks ka and kb (relative to
-// everything, `below` keys lie under the histogram's range).  Results in sh.res.
-// Returns whether both ranks fall inside the histogram.  Ends with a barrier.
-template <int NT, int LOG_NB, bool WRITE_PREF, typename SH>
+// everything; `sh.below` keys lie under the histogram's range, or none if
+// !USE_BELOW).  Clears the histogram, leaves the results in sh.res, returns the
+// below count and whether both ranks fall inside the histogram.  Ends with a barrier.
+template <int NT, int LOG_NB, bool WRITE_PREF, bool USE_BELOW, typename SH>
 __device__ __forceinline__ bool locate(SH& sh, uint32_t tid, uint32_t ka, uint32_t kb,
-                                       uint32_t* total_out) {
+                                       uint32_t* below_out) {
     constexpr int BPT = (1 << LOG_NB) / NT;
     uint32_t loc[BPT], s = 0;
 #pragma unroll
     for (int q = 0; q < BPT; ++q) { loc[q] = sh.hist[tid * BPT + q]; s += loc[q]; }
+#pragma unroll
+    for (int q = 0; q < BPT; ++q) sh.hist[tid * BPT + q] = 0;
     uint32_t total;
     const uint32_t excl = block_excl_scan<NT>(s, tid, sh.wpart, &total);
-    const uint32_t below = sh.below;
+    const uint32_t below = USE_BELOW ? sh.below : 0u;
     const uint32_t ra = ka - below, rb = kb - below;   // wrap when not bracketed
     if (WRITE_PREF) {
         uint32_t p = excl;
@@ -208,7 +222,8 @@ __device__ __forceinline__ bool locate(SH& sh, uint32_t tid, uint32_t ka, uint32
         }
     }
     __syncthreads();
-    *total_out = total;
+    if (USE_BELOW && tid == 0) sh.below = 0;
+    *below_out = rfl(below);
     return rfl(ka >= below && rb < total) != 0;
 }
 
@@ -264,18 +279,16 @@ template <int NT, int ROWS, int LOG_NB, bool WIDE, typename SH, typename Keys>
 __device__ __forceinline__ bool block_select(SH& sh, const Keys& keys, uint32_t skey, bool svalid,
                                              uint32_t n, uint32_t k0, uint32_t k1, uint32_t* out0,
                                              uint32_t* out1, uint32_t* hist_lo = nullptr,
-                                             uint32_t* hist_hi = nullptr, int* hist_shift = nullptr) {
+                                             uint32_t* hist_hi = nullptr, int* hist_shift = nullptr,
+                                             bool hinted = false, uint32_t hint_lo = 0,
+                                             uint32_t hint_hi = 0) {
     constexpr int NB = 1 << LOG_NB;
     constexpr int BPT = NB / NT;
     static_assert(BPT >= 1 && (BPT % 4 == 0 || BPT < 4), "bucket split");
-    uint32_t lo, hi;
-    {   // ---- bracket from the sample
+    uint32_t lo = hint_lo, hi = hint_hi;
+    // Bracket from the sample (skipped while a bracket handed in by the caller holds).
+    auto sample_bracket = [&]() {
         const uint32_t tid = opaque_v(threadIdx.x), lane = tid & (WAVE - 1);
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < BPT; ++q) sh.hist[tid * BPT + q] = 0;
-        if (tid == 0) { sh.below = 0; sh.smin = 0xFFFFFFFFu; sh.smax = 0; }
-        __syncthreads();
         const uint32_t mn = wave_min_to_last(svalid ? skey : 0xFFFFFFFFu);
         const uint32_t mx = wave_max_to_last(svalid ? skey : 0u);
         if (lane == WAVE - 1) { atomicMin(&sh.smin, mn); atomicMax(&sh.smax, mx); }
@@ -285,18 +298,20 @@ __device__ __forceinline__ bool block_select(SH& sh, const Keys& keys, uint32_t 
         const int sshift = shift_for<LOG_NB>(sspan);
         if (svalid) atomicAdd(&sh.hist[(skey - smin) >> sshift], 1u);
         __syncthreads();
+        if (tid == 0) { sh.smin = 0xFFFFFFFFu; sh.smax = 0; }
         // n valid samples: the ranks n/2 -+ (2*sqrt(n) + 1) bracket the column's median
         const uint32_t delta = WIDE ? (n * 87u) >> 8 : (uint32_t)(2.0f * __builtin_sqrtf((float)n)) + 1u;
         const uint32_t half = n / 2;
         const uint32_t ra = half > delta ? half - 1 - delta : 0u;
         const uint32_t rb = min(n - 1, half + delta);
-        uint32_t tot;
-        (void)locate<NT, LOG_NB, false>(sh, tid, ra, rb, &tot);
+        uint32_t unused;
+        (void)locate<NT, LOG_NB, false, false>(sh, tid, ra, rb, &unused);
         const uint32_t ba = rfl(sh.res[0]), bb = rfl(sh.res[2]);
         lo = ra == 0 ? 0u : smin + (ba << sshift);
         const uint64_t hend = (uint64_t)smin + ((uint64_t)(bb + 1) << sshift) - 1;
         hi = rb == n - 1 ? 0xFFFFFFFFu : (hend > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)hend);
-    }
+    };
+    if (!hinted) sample_bracket();
     // mode 0: both statistics together; 1: k0 alone; 2: k1 alone (after a split)
     int mode = 0, rounds = 0;
     uint32_t ka = k0, kb = k1, v0 = 0, v1 = 0;
@@ -308,11 +323,6 @@ __device__ __forceinline__ bool block_select(SH& sh, const Keys& keys, uint32_t 
         // slots, LDS addresses) are then recomputed instead of living in registers
         const uint32_t tid = opaque_v(threadIdx.x);
         const uint32_t lane = tid & (WAVE - 1);
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < BPT; ++q) sh.hist[tid * BPT + q] = 0;
-        if (tid == 0) { sh.below = 0; sh.ncand = 0; }
-        __syncthreads();
         // counting pass
         uint32_t nbelow = 0;   // per lane; summed over the wave after the pass
         {
@@ -333,13 +343,15 @@ __device__ __forceinline__ bool block_select(SH& sh, const Keys& keys, uint32_t 
         nbelow = wave_incl_scan(nbelow);
         if (lane == WAVE - 1 && nbelow) atomicAdd(&sh.below, nbelow);
         __syncthreads();
-        uint32_t total;
-        const bool bracketed = locate<NT, LOG_NB, WIDE>(sh, tid, ka, kb, &total);
-        if (!bracketed) {               // the bracket missed: count over all keys
-            lo = 0; hi = 0xFFFFFFFFu;
+        uint32_t below;
+        const bool bracketed = locate<NT, LOG_NB, WIDE, true>(sh, tid, ka, kb, &below);
+        if (!bracketed) {
+            // the bracket missed: a handed-in one is replaced by the sample's, the
+            // sample's by the full key range
+            if (hinted) { hinted = false; sample_bracket(); }
+            else { lo = 0; hi = 0xFFFFFFFFu; __syncthreads(); }
             continue;
         }
-        const uint32_t below = rfl(sh.below);
         const uint32_t ba = rfl(sh.res[0]), pa = rfl(sh.res[1]);
         const uint32_t bb = rfl(sh.res[2]), pb = rfl(sh.res[3]);
         uint32_t va, vb;
@@ -368,6 +380,7 @@ __device__ __forceinline__ bool block_select(SH& sh, const Keys& keys, uint32_t 
             const uint32_t cnt = min(sh.ncand, (uint32_t)CAND_CAP);
             const uint32_t wa = ka - below - pa, wb = kb - below - pa;
             rank_candidates<NT>(sh, tid, cnt, wa, wb);
+            if (tid == 0) sh.ncand = 0;
             va = rfl(sh.res[4]); vb = rfl(sh.res[5]);
         } else {
             // crowded (ties): look inside bucket ba; if the two statistics sit in
@@ -377,6 +390,7 @@ __device__ __forceinline__ bool block_select(SH& sh, const Keys& keys, uint32_t 
             const uint64_t nend = (uint64_t)nlo + ((uint64_t)1 << shift) - 1;
             hi = nend > hi ? hi : (uint32_t)nend;
             lo = nlo;
+            __syncthreads();
             continue;
         }
         if (mode == 0) {
@@ -384,7 +398,11 @@ __device__ __forceinline__ bool block_select(SH& sh, const Keys& keys, uint32_t 
             if (WIDE && hist_lo) { *hist_lo = lo; *hist_hi = hi; *hist_shift = shift; }
             break;
         }
-        if (mode == 1) { v0 = va; mode = 2; ka = kb = k1; lo = 0; hi = 0xFFFFFFFFu; continue; }
+        if (mode == 1) {
+            v0 = va; mode = 2; ka = kb = k1; lo = 0; hi = 0xFFFFFFFFu;
+            __syncthreads();
+            continue;
+        }
         v1 = va;
         break;
     }
@@ -410,8 +428,6 @@ __device__ __forceinline__ bool mad_from_histogram(SH& sh, const float (&v)[ROWS
     const float xlo = __uint_as_float(lo), xhi = __uint_as_float(hi);
     const float dmax = fminf(med - xlo, xhi - med);
     if (!(dmax > 0.0f) || shift < 2) return false;
-    if (tid == 0) { sh.d1 = 0; sh.d2 = 0xFFFFFFFFu; sh.ncand = 0; sh.below = 0; }
-    __syncthreads();
     {
         // Pairs of bucket edges (eL, eR) with value(eL) <= med < value(eR): the set
         // S = {eL <= key < eR} is counted exactly by the prefix sums, every value
@@ -461,7 +477,11 @@ __device__ __forceinline__ bool mad_from_histogram(SH& sh, const float (&v)[ROWS
     }
     __syncthreads();
     const uint32_t d1 = rfl(sh.d1), d2 = rfl(sh.d2);
-    if (d2 == 0xFFFFFFFFu || d2 < d1) return false;
+    if (d2 == 0xFFFFFFFFu || d2 < d1) {
+        __syncthreads();                     // everyone has read d1, d2
+        if (tid == 0) { sh.d1 = 0; sh.d2 = 0xFFFFFFFFu; }
+        return false;
+    }
     // exact pass: count |x - med| below d1, gather those in [d1, d2]
     const uint32_t span = d2 - d1;
     uint32_t nbelow = 0;
@@ -485,10 +505,16 @@ __device__ __forceinline__ bool mad_from_histogram(SH& sh, const float (&v)[ROWS
     nbelow = wave_incl_scan(nbelow);
     if (lane == WAVE - 1 && nbelow) atomicAdd(&sh.below, nbelow);
     __syncthreads();
+    if (tid == 0) { sh.d1 = 0; sh.d2 = 0xFFFFFFFFu; }
     const uint32_t below = rfl(sh.below), cnt = rfl(sh.ncand);
-    if (cnt > (uint32_t)CAND_CAP || below > k0 || k1 >= below + cnt) return false;
+    if (cnt > (uint32_t)CAND_CAP || below > k0 || k1 >= below + cnt) {
+        __syncthreads();                     // everyone has read the counters
+        if (tid == 0) { sh.below = 0; sh.ncand = 0; }
+        return false;
+    }
     const uint32_t wa = k0 - below, wb = k1 - below;
     rank_candidates<NT>(sh, tid, cnt, wa, wb);
+    if (tid == 0) { sh.below = 0; sh.ncand = 0; }
     *out0 = rfl(sh.res[4]);
     *out1 = rfl(sh.res[5]);
     return true;
@@ -617,7 +643,13 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
     auto fresh_tid4 = [&]() -> uint32_t { return opaque_v((uint32_t)tid * 4); };
 
     uint32_t NE[(ROWS + 3) / 4]; // node mask byte per row, packed
-    if (tid == 0) { sh.umax[0] = 0; sh.umax[1] = 0; sh.ncand = 0; }
+    // the selection's work area starts in its rest state (see the LDS protocol)
+    for (int i = tid; i < SH::NB; i += NT) sh.hist[i] = 0;
+    if (tid == 0) {
+        sh.umax[0] = 0; sh.umax[1] = 0; sh.ncand = 0; sh.below = 0;
+        sh.smin = 0xFFFFFFFFu; sh.smax = 0; sh.d1 = 0; sh.d2 = 0xFFFFFFFFu;
+        for (int m = 0; m < 8; ++m) sh.hok[m] = 0;
+    }
     __syncthreads();
     // number of threads whose sampled element (row 0) is a real rank
     uint32_t nsample = NT;
@@ -626,6 +658,9 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
         if (lane == 0) atomicAdd(&sh.ncand, c);
         __syncthreads();
         nsample = rfl(sh.ncand);
+        __syncthreads();
+        if (tid == 0) sh.ncand = 0;
+        __syncthreads();
     }
 
     const uint32_t k0 = R / 2 - 1, k1 = R / 2;   // R is even
@@ -684,14 +719,38 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
         float med;
         bool have_mad = false;
         if (!signs) {
+            // A workgroup scores consecutive steps, and telemetry moves little from one
+            // step to the next: the previous step's median of this metric, with the
+            // reach its histogram had, brackets this step's counting pass without
+            // sampling.  A bracket that misses is noticed and replaced by the sample's.
+            bool hinted = rfl(sh.hok[m]) != 0;
+            uint32_t hint_lo = 0, hint_hi = 0;
+            if (hinted) {
+                const float xl = sh.hmed[m] - sh.hwl[m], xh = sh.hmed[m] + sh.hwh[m];
+                hint_lo = rfl(__float_as_uint(xl));
+                hint_hi = rfl(__float_as_uint(xh));
+                hinted = xl >= 0.0f && xh > xl && hint_hi < 0x7F800000u;
+            }
             uint32_t hlo = 0, hhi = 0;
             int hshift = 0;
             const bool one_round = block_select<NT, ROWS, LOG_NB, true>(
                 sh, XKeys<ROWS, true>{v}, __float_as_uint(v[0][0]), svalid, nsample, k0, k1, &s0, &s1,
-                &hlo, &hhi, &hshift);
+                &hlo, &hhi, &hshift, hinted, hint_lo, hint_hi);
             med = 0.5f * (__uint_as_float(s0) + __uint_as_float(s1));
             if (one_round)
                 have_mad = mad_from_histogram<NT, ROWS, LOG_NB>(sh, v, med, hlo, hhi, hshift, k0, k1, &s0, &s1);
+            if (tid == 0) {
+                if (have_mad) {                 // keep the reach, follow the median
+                    if (!hinted) {
+                        sh.hwl[m] = med - __uint_as_float(hlo);
+                        sh.hwh[m] = __uint_as_float(hhi) - med;
+                    }
+                    sh.hmed[m] = med;
+                    sh.hok[m] = 1;
+                } else {
+                    sh.hok[m] = 0;
+                }
+            }
         } else {
             block_select<NT, ROWS, LOG_NB, false>(sh, XKeys<ROWS, false>{v}, key_of(v[0][0] + 0.0f),
                                                   svalid, nsample, k0, k1, &s0, &s1);
