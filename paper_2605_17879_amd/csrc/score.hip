@@ -53,7 +53,7 @@ struct Shared {
     uint32_t res[6];           // ba, prefix before ba, bb, prefix through bb, va, vb
     // Per metric, from the previous step scored by this workgroup: the median and how
     // far below / above it the counting histogram reached (hok = the hint is usable).
-    float hmed[8], hwl[8], hwh[8];
+    float hmed[8], hwl[8], hwh[8], hmad[8];
     uint32_t hok[8];
     uint8_t nodeb[MAX_NODES];
 };
@@ -422,13 +422,18 @@ __device__ __forceinline__ bool block_select(SH& sh, const Keys& keys, uint32_t 
 template <int NT, int ROWS, int LOG_NB, typename SH>
 __device__ __forceinline__ bool mad_from_histogram(SH& sh, const float (&v)[ROWS][4], float med,
                                                    uint32_t lo, uint32_t hi, int shift, uint32_t k0,
-                                                   uint32_t k1, uint32_t* out0, uint32_t* out1) {
+                                                   uint32_t k1, float mad_hint, uint32_t* out0,
+                                                   uint32_t* out1) {
     constexpr int NB = 1 << LOG_NB;
     const uint32_t tid = opaque_v(threadIdx.x), lane = tid & (WAVE - 1);
     const float xlo = __uint_as_float(lo), xhi = __uint_as_float(hi);
     const float dmax = fminf(med - xlo, xhi - med);
     if (!(dmax > 0.0f) || shift < 2) return false;
-    {
+    // With the previous step's MAD of this metric as a hint only the edges whose
+    // distance from the median is within an eighth of it are paired (a few waves'
+    // worth); if they do not enclose the ranks, all edges are.
+    uint32_t d1 = 0, d2 = 0;
+    auto grid = [&](bool near_hint_only) -> bool {
         // Pairs of bucket edges (eL, eR) with value(eL) <= med < value(eR): the set
         // S = {eL <= key < eR} is counted exactly by the prefix sums, every value
         // outside S is at least min(dL, dR) away from med and every value inside at
@@ -455,6 +460,7 @@ __device__ __forceinline__ bool mad_from_histogram(SH& sh, const float (&v)[ROWS
         for (int q = 0; q < BPT; ++q) {
             const uint32_t b = tid * BPT + q;
             const float xe = edge(b);
+            if (near_hint_only && !(fabsf(fabsf(xe - med) - mad_hint) <= 0.125f * mad_hint)) continue;
             if (xe > med) {            // a right edge: mirror it to the left
                 const uint32_t km = __float_as_uint(med - (xe - med));
                 if (km >= lo && km <= hi) {
@@ -474,14 +480,19 @@ __device__ __forceinline__ bool mad_from_histogram(SH& sh, const float (&v)[ROWS
         c1 = wave_max_to_last(c1);
         c2 = wave_min_to_last(c2);
         if (lane == WAVE - 1) { atomicMax(&sh.d1, c1); atomicMin(&sh.d2, c2); }
-    }
-    __syncthreads();
-    const uint32_t d1 = rfl(sh.d1), d2 = rfl(sh.d2);
-    if (d2 == 0xFFFFFFFFu || d2 < d1) {
+        __syncthreads();
+        d1 = rfl(sh.d1); d2 = rfl(sh.d2);
+        if (d2 != 0xFFFFFFFFu && d2 >= d1) return true;
         __syncthreads();                     // everyone has read d1, d2
         if (tid == 0) { sh.d1 = 0; sh.d2 = 0xFFFFFFFFu; }
         return false;
+    };
+    bool found = mad_hint > 0.0f && grid(true);
+    if (!found) {
+        if (mad_hint > 0.0f) __syncthreads();    // the reset above precedes the next proposals
+        found = grid(false);
     }
+    if (!found) return false;
     // exact pass: count |x - med| below d1, gather those in [d1, d2]
     const uint32_t span = d2 - d1;
     uint32_t nbelow = 0;
@@ -738,7 +749,8 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
                 &hlo, &hhi, &hshift, hinted, hint_lo, hint_hi);
             med = 0.5f * (__uint_as_float(s0) + __uint_as_float(s1));
             if (one_round)
-                have_mad = mad_from_histogram<NT, ROWS, LOG_NB>(sh, v, med, hlo, hhi, hshift, k0, k1, &s0, &s1);
+                have_mad = mad_from_histogram<NT, ROWS, LOG_NB>(sh, v, med, hlo, hhi, hshift, k0, k1,
+                                                                hinted ? sh.hmad[m] : 0.0f, &s0, &s1);
             if (tid == 0) {
                 if (have_mad) {                 // keep the reach, follow the median
                     if (!hinted) {
@@ -746,6 +758,7 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
                         sh.hwh[m] = __uint_as_float(hhi) - med;
                     }
                     sh.hmed[m] = med;
+                    sh.hmad[m] = 0.5f * (__uint_as_float(s0) + __uint_as_float(s1));
                     sh.hok[m] = 1;
                 } else {
                     sh.hok[m] = 0;
@@ -874,13 +887,15 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
         const bool valid = FULL || rbase(j, to) < R;
         const uint32_t Ej = emask[j * NT + to / 4];
         if (valid) *reinterpret_cast<uint32_t*>(erow + rbase(j, to)) = Ej;
-        uint32_t nib = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t b = (Ej >> (8 * i)) & 0xFFu;
-            const bool an = ((b >> a.primary) & 1u) && (uint32_t)__popc(b) >= a.min_signals;
-            nib |= (an && valid ? 1u : 0u) << i;
-        }
+        // multi-signal rule on the four mask bytes at once: primary bit set and
+        // per-byte popcount >= min_signals (adding 0x80 - min_signals carries into bit 7)
+        const uint32_t prim_set = (Ej >> a.primary) & 0x01010101u;
+        uint32_t pc = Ej - ((Ej >> 1) & 0x55555555u);
+        pc = (pc & 0x33333333u) + ((pc >> 2) & 0x33333333u);
+        pc = (pc + (pc >> 4)) & 0x0F0F0F0Fu;
+        const uint32_t enough = ((pc + (0x80u - a.min_signals) * 0x01010101u) >> 7) & 0x01010101u;
+        const uint32_t an = valid ? (prim_set & enough) : 0u;
+        const uint32_t nib = (an | (an >> 7) | (an >> 14) | (an >> 21)) & 0xFu;
         // 16 consecutive lanes hold one 64-bit word
         const int sub = lane & 15;
         uint32_t wlo = sub < 8 ? nib << (4 * sub) : 0u;
