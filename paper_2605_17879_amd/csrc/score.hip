@@ -275,13 +275,19 @@ __device__ __forceinline__ int shift_for(uint32_t span) {
 // the first counting pass settles the selection, *hist_lo / *hist_shift describe
 // that histogram (bucket b holds keys hist_lo + b*2^shift ...) and the function
 // returns true; the MAD shortcut then reads the prefix sums.
+//
+// umax_slot (with a handed-in bracket only): the first counting pass also finds the
+// largest raw bit pattern of the column and leaves it in *umax_out.  Should it carry
+// a sign bit, the raw bits were no valid keys: the selection stops after clearing
+// its work area and the caller starts over with order-preserving keys.
 template <int NT, int ROWS, int LOG_NB, bool WIDE, typename SH, typename Keys>
 __device__ __forceinline__ bool block_select(SH& sh, const Keys& keys, uint32_t skey, bool svalid,
                                              uint32_t n, uint32_t k0, uint32_t k1, uint32_t* out0,
                                              uint32_t* out1, uint32_t* hist_lo = nullptr,
                                              uint32_t* hist_hi = nullptr, int* hist_shift = nullptr,
                                              bool hinted = false, uint32_t hint_lo = 0,
-                                             uint32_t hint_hi = 0) {
+                                             uint32_t hint_hi = 0, uint32_t* umax_slot = nullptr,
+                                             uint32_t* umax_out = nullptr) {
     constexpr int NB = 1 << LOG_NB;
     constexpr int BPT = NB / NT;
     static_assert(BPT >= 1 && (BPT % 4 == 0 || BPT < 4), "bucket split");
@@ -325,6 +331,8 @@ __device__ __forceinline__ bool block_select(SH& sh, const Keys& keys, uint32_t 
         const uint32_t lane = tid & (WAVE - 1);
         // counting pass
         uint32_t nbelow = 0;   // per lane; summed over the wave after the pass
+        const bool with_umax = umax_slot != nullptr && rounds == 1;
+        uint32_t um = 0;
         {
             const uint32_t tok = keys.token();
 #pragma unroll
@@ -336,13 +344,37 @@ __device__ __forceinline__ bool block_select(SH& sh, const Keys& keys, uint32_t 
                     const uint32_t t = kk - lo;
                     if (t <= span) atomicAdd(&sh.hist[t >> shift], 1u);
                 }
+                if (umax_slot != nullptr) {     // (padding lanes never take this route: FULL tilings only)
+                    // the row's registers are made opaque here, or the maxima, which do not
+                    // depend on the round, are all computed ahead of the loop -- after
+                    // waiting for the whole column instead of row by row
+                    float(&row)[4] = const_cast<float(&)[4]>(keys.v[j]);
+                    asm volatile("" : "+v"(row[0]), "+v"(row[1]), "+v"(row[2]), "+v"(row[3]));
+                    um = max(um, max(keys.at(j, 0, tok), keys.at(j, 1, tok)));
+                    um = max(um, max(keys.at(j, 2, tok), keys.at(j, 3, tok)));
+                    asm volatile("" : "+v"(um));
+                }
                 asm volatile("" : "+v"(nbelow));
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
         nbelow = wave_incl_scan(nbelow);
-        if (lane == WAVE - 1 && nbelow) atomicAdd(&sh.below, nbelow);
+        if (with_umax) um = wave_max_to_last(um);
+        if (lane == WAVE - 1) {
+            if (nbelow) atomicAdd(&sh.below, nbelow);
+            if (with_umax) atomicMax(umax_slot, um);
+        }
         __syncthreads();
+        if (with_umax) {
+            const uint32_t umax = rfl(*umax_slot);
+            *umax_out = umax;
+            if (umax >= 0x80000000u) {
+                uint32_t unused;
+                (void)locate<NT, LOG_NB, false, true>(sh, tid, ka, kb, &unused);   // clears the work area
+                *out0 = 0; *out1 = 0;
+                return false;
+            }
+        }
         uint32_t below;
         const bool bracketed = locate<NT, LOG_NB, WIDE, true>(sh, tid, ka, kb, &below);
         if (!bracketed) {
@@ -430,8 +462,8 @@ __device__ __forceinline__ bool mad_from_histogram(SH& sh, const float (&v)[ROWS
     const float dmax = fminf(med - xlo, xhi - med);
     if (!(dmax > 0.0f) || shift < 2) return false;
     // With the previous step's MAD of this metric as a hint only the edges whose
-    // distance from the median is within an eighth of it are paired (a few waves'
-    // worth); if they do not enclose the ranks, all edges are.
+    // distance from the median is within an eighth of it are paired (a couple of
+    // hundred, one per thread); if they do not enclose the ranks, all edges are.
     uint32_t d1 = 0, d2 = 0;
     auto grid = [&](bool near_hint_only) -> bool {
         // Pairs of bucket edges (eL, eR) with value(eL) <= med < value(eR): the set
@@ -456,11 +488,8 @@ __device__ __forceinline__ bool mad_from_histogram(SH& sh, const float (&v)[ROWS
                 }
             }
         };
-#pragma unroll
-        for (int q = 0; q < BPT; ++q) {
-            const uint32_t b = tid * BPT + q;
+        auto pair_edge = [&](uint32_t b) {
             const float xe = edge(b);
-            if (near_hint_only && !(fabsf(fabsf(xe - med) - mad_hint) <= 0.125f * mad_hint)) continue;
             if (xe > med) {            // a right edge: mirror it to the left
                 const uint32_t km = __float_as_uint(med - (xe - med));
                 if (km >= lo && km <= hi) {
@@ -476,6 +505,20 @@ __device__ __forceinline__ bool mad_from_histogram(SH& sh, const float (&v)[ROWS
                     eval(b, br + 1);
                 }
             }
+        };
+        if (near_hint_only) {
+            // the edges within an eighth of the hint around med - hint and med + hint,
+            // dealt out one per thread
+            const float wl0 = med - 1.125f * mad_hint, wl1 = med - 0.875f * mad_hint;
+            const float wr0 = med + 0.875f * mad_hint, wr1 = med + 1.125f * mad_hint;
+            const uint32_t klo = __float_as_uint(fmaxf(wl0, xlo)), khi = __float_as_uint(fminf(wr1, xhi));
+            const uint32_t bl0 = (klo - lo) >> shift, bl1 = (__float_as_uint(fmaxf(wl1, xlo)) - lo) >> shift;
+            const uint32_t br0 = (__float_as_uint(fminf(wr0, xhi)) - lo) >> shift, br1 = (khi - lo) >> shift;
+            const uint32_t nl = bl1 - bl0 + 1, nr = br1 - br0 + 1;
+            for (uint32_t e = tid; e < nl + nr; e += NT) pair_edge(e < nl ? bl0 + e : br0 + (e - nl));
+        } else {
+#pragma unroll
+            for (int q = 0; q < BPT; ++q) pair_edge(tid * BPT + q);
         }
         c1 = wave_max_to_last(c1);
         c2 = wave_min_to_last(c2);
@@ -675,6 +718,7 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
     }
 
     const uint32_t k0 = R / 2 - 1, k1 = R / 2;   // R is even
+    uint32_t colpar = 0;                          // parity of the column count: which umax slot is in use
 
     float v[ROWS][4];
     // Issue the loads of one register row of a column (padding: a NaN, whose key
@@ -692,8 +736,13 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
     {
         const uint32_t tl = fresh_tid4();
         const float* col = a.x + (size_t)t_begin * M * R;
+        // issued in row order, like the refills of the score loop: the waits of the
+        // first pass over a column are then placed row by row
 #pragma unroll
-        for (int j = 0; j < ROWS; ++j) load_row(j, col, tl);
+        for (int j = 0; j < ROWS; ++j) {
+            load_row(j, col, tl);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 
     for (size_t t = t_begin; t < t_end; ++t) {
@@ -709,44 +758,53 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
         const float* next_col = a.x + (t * M + m + (have_next ? 1 : 0)) * (size_t)R;
         const uint32_t tl = fresh_tid4();
         const bool svalid = FULL || rbase(0, tl) < R;
+        // A workgroup scores consecutive steps, and telemetry moves little from one
+        // step to the next: the previous step's median of this metric, with the
+        // reach its histogram had, brackets this step's counting pass without
+        // sampling.  A bracket that misses is noticed and replaced by the sample's.
+        bool hinted = rfl(sh.hok[m]) != 0;
+        uint32_t hint_lo = 0, hint_hi = 0;
+        if (hinted) {
+            const float xl = sh.hmed[m] - sh.hwl[m], xh = sh.hmed[m] + sh.hwh[m];
+            hint_lo = rfl(__float_as_uint(xl));
+            hint_hi = rfl(__float_as_uint(xh));
+            hinted = xl >= 0.0f && xh > xl && hint_hi < 0x7F800000u;
+        }
         // Largest raw bit pattern of the column: >= 0x80000000 iff some value carries
         // a sign bit (negative or -0); otherwise it is the bit pattern of the maximum.
-        uint32_t um = 0;
+        // With a hint the column is taken to be sign-free like its predecessor and the
+        // maximum is found by the median's counting pass itself, which starts on the
+        // register rows as they arrive; otherwise it takes a pass of its own.
+        const bool fused_umax = FULL && hinted;
+        uint32_t* const umax_slot = &sh.umax[colpar];
+        uint32_t umax = 0;
+        if (!fused_umax) {
+            uint32_t um = 0;
 #pragma unroll
-        for (int j = 0; j < ROWS; ++j) {
-            if (FULL || rbase(j, tl) < R) {
-                um = max(um, max(__float_as_uint(v[j][0]), __float_as_uint(v[j][1])));
-                um = max(um, max(__float_as_uint(v[j][2]), __float_as_uint(v[j][3])));
+            for (int j = 0; j < ROWS; ++j) {
+                if (FULL || rbase(j, tl) < R) {
+                    um = max(um, max(__float_as_uint(v[j][0]), __float_as_uint(v[j][1])));
+                    um = max(um, max(__float_as_uint(v[j][2]), __float_as_uint(v[j][3])));
+                }
             }
+            um = wave_max_to_last(um);
+            if (lane == WAVE - 1) atomicMax(umax_slot, um);
+            __syncthreads();
+            umax = rfl(*umax_slot);
         }
-        um = wave_max_to_last(um);
-        if (lane == WAVE - 1) atomicMax(&sh.umax[m & 1], um);
-        __syncthreads();
-        if (tid == 0) sh.umax[(m + 1) & 1] = 0;
-        const uint32_t umax = rfl(sh.umax[m & 1]);
-        const bool signs = umax >= 0x80000000u;
+        bool signs = umax >= 0x80000000u;
 
         uint32_t s0, s1;
         float med;
         bool have_mad = false;
         if (!signs) {
-            // A workgroup scores consecutive steps, and telemetry moves little from one
-            // step to the next: the previous step's median of this metric, with the
-            // reach its histogram had, brackets this step's counting pass without
-            // sampling.  A bracket that misses is noticed and replaced by the sample's.
-            bool hinted = rfl(sh.hok[m]) != 0;
-            uint32_t hint_lo = 0, hint_hi = 0;
-            if (hinted) {
-                const float xl = sh.hmed[m] - sh.hwl[m], xh = sh.hmed[m] + sh.hwh[m];
-                hint_lo = rfl(__float_as_uint(xl));
-                hint_hi = rfl(__float_as_uint(xh));
-                hinted = xl >= 0.0f && xh > xl && hint_hi < 0x7F800000u;
-            }
             uint32_t hlo = 0, hhi = 0;
             int hshift = 0;
             const bool one_round = block_select<NT, ROWS, LOG_NB, true>(
                 sh, XKeys<ROWS, true>{v}, __float_as_uint(v[0][0]), svalid, nsample, k0, k1, &s0, &s1,
-                &hlo, &hhi, &hshift, hinted, hint_lo, hint_hi);
+                &hlo, &hhi, &hshift, hinted, hint_lo, hint_hi, fused_umax ? umax_slot : nullptr, &umax);
+            signs = umax >= 0x80000000u;       // (only the fused pass can find this out here)
+        if (!signs) {
             med = 0.5f * (__uint_as_float(s0) + __uint_as_float(s1));
             if (one_round)
                 have_mad = mad_from_histogram<NT, ROWS, LOG_NB>(sh, v, med, hlo, hhi, hshift, k0, k1,
@@ -764,7 +822,13 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
                     sh.hok[m] = 0;
                 }
             }
-        } else {
+        }
+        }
+        // the other slot is free again: every thread read it a column ago
+        if (tid == 0) sh.umax[colpar ^ 1u] = 0;
+        colpar ^= 1u;
+        if (signs) {
+            if (tid == 0) sh.hok[m] = 0;
             block_select<NT, ROWS, LOG_NB, false>(sh, XKeys<ROWS, false>{v}, key_of(v[0][0] + 0.0f),
                                                   svalid, nsample, k0, k1, &s0, &s1);
             med = 0.5f * (float_of_key(s0) + float_of_key(s1));
