@@ -8,7 +8,8 @@
 //
 // One thread owns one item and one wave owns one 64-item word column of the
 // ring, so every ring word is read and written by a single wave.  A wave takes
-// 64 steps at a time: lane l fetches the word entering at step s0 + l and the
+// 64 steps at a time (fetched a few blocks ahead): lane l fetches the word
+// entering at step s0 + l and the
 // word leaving the window at that step (the one that entered W steps earlier,
 // from the batch itself when recent enough, else from the ring).  Two 64x64 bit
 // transposes across the lanes turn them into per-item time vectors, so a block
@@ -55,27 +56,35 @@ __global__ __launch_bounds__(WIN_NT) void window_kernel(const gd_window_args a) 
 
     uint32_t c = live ? count[item] : 0;
     int32_t f = live ? first[item] : 0;
-    uint64_t win, wout;
-    fetch(lane, &win, &wout);
-    for (uint32_t s0 = 0; s0 < T; s0 += WAVE) {
-        uint64_t win_n, wout_n;                       // the next block is fetched ahead
-        fetch(s0 + WAVE + lane, &win_n, &wout_n);
-        // bit j of `in` / `out`: does this item enter / leave as anomalous at step s0 + j
-        const uint64_t in = gd_transpose64(win, lane);
-        const uint64_t out = gd_transpose64(wout, lane);
-        const uint32_t pin = __popcll(in), pout = __popcll(out);
-        if (f == 0 && c + pin >= K) {                 // the flag may first rise inside this block
-            const uint32_t n = min((uint32_t)WAVE, T - s0);
-            for (uint32_t j = 0; j < n; ++j) {
-                const uint64_t upto = (2ull << j) - 1;
-                if (c + __popcll(in & upto) - __popcll(out & upto) >= K) {
-                    f = (int32_t)(a.first_step + s0 + j) + 1;
-                    break;
+    // Blocks are fetched AHEAD blocks in advance (the loop is latency-bound: one wave
+    // per word column walks its steps in order).
+    constexpr int AHEAD = 4;
+    uint64_t win[AHEAD], wout[AHEAD];
+#pragma unroll
+    for (int q = 0; q < AHEAD; ++q) fetch(q * WAVE + lane, &win[q], &wout[q]);
+    for (uint32_t s0 = 0; s0 < T; s0 += AHEAD * WAVE) {
+#pragma unroll
+        for (int q = 0; q < AHEAD; ++q) {
+            const uint32_t sq = s0 + q * WAVE;        // uniform over the wave
+            if (sq >= T) break;
+            const uint64_t wi = win[q], wo = wout[q];
+            fetch(sq + AHEAD * WAVE + lane, &win[q], &wout[q]);
+            // bit j of `in` / `out`: does this item enter / leave as anomalous at step sq + j
+            const uint64_t in = gd_transpose64(wi, lane);
+            const uint64_t out = gd_transpose64(wo, lane);
+            const uint32_t pin = __popcll(in), pout = __popcll(out);
+            if (f == 0 && c + pin >= K) {             // the flag may first rise inside this block
+                const uint32_t n = min((uint32_t)WAVE, T - sq);
+                for (uint32_t j = 0; j < n; ++j) {
+                    const uint64_t upto = (2ull << j) - 1;
+                    if (c + __popcll(in & upto) - __popcll(out & upto) >= K) {
+                        f = (int32_t)(a.first_step + sq + j) + 1;
+                        break;
+                    }
                 }
             }
+            c += pin - pout;
         }
-        c += pin - pout;
-        win = win_n; wout = wout_n;
     }
     if (live) {
         count[item] = (uint16_t)c;
