@@ -196,6 +196,31 @@ def test_device_division_is_correctly_rounded():
     det.close()
 
 
+@pytest.mark.parametrize("R", [64, 4096, 65536])
+def test_topk_request_sizes(R):
+    """k from 1 to N: the short-list route (k <= 64) and the full sort, with many
+    equal window counts and equal scores among the keys."""
+    say(f"case top-k sizes R={R}")
+    T, M = 12, 2
+    g = torch.Generator().manual_seed(R + 1)
+    x = torch.exp(0.02 * torch.randn((T, M, R), generator=g, dtype=torch.float64)).to(torch.float32)
+    x[:, :, : R // 2] = x[:, :, R // 2:]                # every node score appears twice
+    x[4:, :, 8:24] *= 1.3                               # two nodes with window counts > 0
+    p = oracle_params(R=R, M=M, W=6, k=3, directions=(1, 1), min_signals=1)
+    d = oracle.detect(p, x.numpy(), topk_k=1)
+    det = detector_for(p)
+    gscore = gpu_score(det, x, want_z=False)
+    det.update_window(gscore, T)
+    N = R // 8
+    from gpu_harness import gpu_topk
+    for k in sorted({1, 2, min(7, N), min(63, N), min(64, N), min(65, N), min(200, N), N}):
+        want_idx, want_key = oracle.topk(d["nodes"].count, d["scores"].node_z[-1], k)
+        idx, key = gpu_topk(det, k)
+        assert np.array_equal(idx, want_idx), f"k={k}: indices"
+        assert np.array_equal(key, want_key), f"k={k}: keys"
+    det.close()
+
+
 def _full_size_case(w, seed, chunk, min_flagged_nodes):
     """Score the whole workload in ONE gd_score_batch call on GPU-generated data,
     then window / flags / top-k.  The oracle scores every step of the same bytes
