@@ -10,7 +10,9 @@ Parity pins (all in ``tests/test_oracle_*.py``): brute-force counting median
 on tiny columns, ``numpy.median`` on float32, closed forms on ramps, a worked
 8-rank column, power-of-two rescaling, rank permutation, noise-free data,
 stragglers injected with a constructed margin, spike immunity, brute-force
-top-k.  No function here is "parity unpinned".
+top-k; for the severity tiers: exact rational arithmetic on small cases,
+``numpy.median`` of the quotients, constructed slowdowns, the window's extent,
+both directions, tier boundaries.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -68,6 +70,9 @@ def _load():
         _lib.go_node_flag_byte.restype = None
         _lib.go_topk.argtypes = [ctypes.c_uint32, vp, vp, ctypes.c_uint32, vp, vp]
         _lib.go_topk.restype = None
+        _lib.go_severity.argtypes = [ctypes.POINTER(_Cfg), vp, ctypes.c_uint64, vp, vp,
+                                     ctypes.c_float, ctypes.c_float, vp, vp]
+        _lib.go_severity.restype = None
     return _lib
 
 
@@ -210,6 +215,24 @@ def topk(node_count: np.ndarray, node_z_last: np.ndarray, k: int):
     key = np.empty(k, np.uint64)
     _load().go_topk(N, _ptr(node_count), _ptr(node_z_last), k, _ptr(idx), _ptr(key))
     return idx, key
+
+
+def severity(p: Params, x: np.ndarray, med: np.ndarray, node_flag_byte: np.ndarray,
+             moderate: float = 0.10, severe: float = 0.20):
+    """(slowdown[N] f32, tier[N] u8) of the flagged nodes over the last min(T, W) steps of x."""
+    x = np.ascontiguousarray(x, np.float32)
+    T, M, R = x.shape
+    assert (M, R) == (p.M, p.R)
+    med = np.ascontiguousarray(med, np.float32)
+    assert med.shape == (T, M)
+    nfb = np.ascontiguousarray(node_flag_byte, np.uint8)
+    assert nfb.shape == (p.N,)
+    slow = np.empty(p.N, np.float32)
+    tier = np.empty(p.N, np.uint8)
+    c = p._c()
+    _load().go_severity(ctypes.byref(c), _ptr(x), T, _ptr(med), _ptr(nfb), moderate, severe,
+                        _ptr(slow), _ptr(tier))
+    return slow, tier
 
 
 def detect(p: Params, x: np.ndarray, topk_k: int, want_z: bool = False):

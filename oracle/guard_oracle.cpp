@@ -16,6 +16,8 @@
 //     windows                                           -> go_window
 //   * the unit acted upon is the 8-GPU node (Section 7.1) -> node scores,
 //                                                          go_flags, go_topk
+//   * the response to a flagged node depends on how much it slows the job
+//     (none / about 10% / 20% or more)                  -> go_severity
 // The estimators and constants (median, MAD x 1.4826, threshold, k-of-W,
 // scaled node sum, ranking key) are this repository's stated reading of those
 // sentences; each function says which rule it implements.
@@ -258,6 +260,47 @@ void go_topk(uint32_t N, const uint16_t* node_count, const float* node_z_last, u
         idx[j] = (int32_t)n;
         key[j] = ((uint64_t)node_count[n] << 48) |
                  ((uint64_t)order_key(canon(node_z_last[n])) << 16) | (uint64_t)(0xFFFFu - n);
+    }
+}
+
+// Severity of the performance impact of a flagged node (Section 4.2, the tiered
+// response: no observable impact / moderate, sustained slowdown of about 10% /
+// severe degradation of 20% or more).  Reading: over the last min(T, W) steps of
+// the history x[t][m][r], every sample of the node's G GPUs in the primary metric
+// is divided by that step's cross-rank median (med[t][M] as go_score wrote it);
+// a lower-is-worse primary divides the other way round, a two-sided one takes
+// whichever quotient is >= 1.  The node's slowdown is the median of those
+// min(T, W) * G quotients (rule "median") minus 1, each operation rounded to fp32.
+//   tier 0: node_flag_byte[n] == 0 (not flagged; slowdown reported as 0)
+//   tier 1: flagged, slowdown <  moderate           ("pending verification")
+//   tier 2: flagged, moderate <= slowdown < severe  (mitigate at next checkpoint)
+//   tier 3: flagged, slowdown >= severe             (replace the node now)
+void go_severity(const go_config* c, const float* x, uint64_t T, const float* med,
+                 const uint8_t* node_flag_byte, float moderate, float severe, float* slowdown,
+                 uint8_t* tier) {
+    const uint32_t R = c->n_ranks, G = c->gpus_per_node, M = c->n_metrics, N = R / G;
+    const uint32_t p = c->primary_metric;
+    const int dir = c->direction[p];
+    const uint64_t Ws = T < c->window ? T : c->window;
+    for (uint32_t n = 0; n < N; ++n) {
+        slowdown[n] = 0.0f;
+        tier[n] = 0;
+        if (!node_flag_byte[n] || Ws == 0) continue;
+        std::vector<float> q;
+        for (uint64_t t = T - Ws; t < T; ++t) {
+            const float m = med[t * M + p];
+            for (uint32_t g = 0; g < G; ++g) {
+                const float xv = canon(x[(t * M + p) * (uint64_t)R + (uint64_t)n * G + g]);
+                float r;
+                if (dir > 0) r = xv / m;
+                else if (dir < 0) r = m / xv;
+                else r = xv >= m ? xv / m : m / xv;
+                q.push_back(r);
+            }
+        }
+        const float s = median_by_sort(q) - 1.0f;
+        slowdown[n] = s;
+        tier[n] = s >= severe ? 3 : (s >= moderate ? 2 : 1);
     }
 }
 
