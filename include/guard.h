@@ -165,6 +165,28 @@ gd_status gd_flags(gd_handle h, uint8_t* d_rank_flag, uint16_t* d_rank_count,
  */
 gd_status gd_topk_nodes(gd_handle h, uint32_t k, int32_t* d_idx, uint64_t* d_key, void* stream);
 
+/*
+ * Severity of the performance impact of the flagged nodes (Section 4.2, the
+ * tiered response: no observable impact / a moderate, sustained slowdown of
+ * about 10% / severe degradation of 20% or more).  Call after gd_update_window
+ * has consumed the same T steps: a node counts as flagged when its own window
+ * count or that of one of its 8 ranks has reached persist_k.  For a flagged node,
+ * each of its 8 primary-metric samples of the last min(T, window) steps of d_x is
+ * divided by that step's median d_med[t][primary] (the other way round when the
+ * primary metric is lower-is-worse; whichever quotient is >= 1 when it is
+ * two-sided; -0 reads as +0); the slowdown is the median of these quotients (the
+ * two middle ones added, then halved) minus 1, every operation rounded to fp32.
+ *   d_x   [T][M][R] device, the batch gd_score_batch scored
+ *   d_med [T][M]    device, the medians it wrote
+ *   d_node_slowdown [N] f32 device: the slowdown, 0 for a node that is not flagged
+ *   d_node_tier     [N] u8  device: 0 not flagged; 1 slowdown < moderate;
+ *                            2 moderate <= slowdown < severe; 3 slowdown >= severe
+ * moderate > severe is GD_ERR_INVALID_ARG.  T == 0 reports tier 0 everywhere.
+ * Zero or non-finite medians or samples give an unspecified slowdown for that node.
+ */
+gd_status gd_severity(gd_handle h, const float* d_x, uint32_t T, const float* d_med, float moderate,
+                      float severe, float* d_node_slowdown, uint8_t* d_node_tier, void* stream);
+
 /* Text of the last error on this handle (or of the last failed gd_create when
  * h is NULL).  The pointer stays valid until the next call on the handle. */
 const char* gd_last_error(gd_handle h);

@@ -222,6 +222,28 @@ gd_status gd_topk_nodes(gd_handle h, uint32_t k, int32_t* d_idx, uint64_t* d_key
     return GD_OK;
 }
 
+gd_status gd_severity(gd_handle h, const float* d_x, uint32_t T, const float* d_med, float moderate,
+                      float severe, float* d_node_slowdown, uint8_t* d_node_tier, void* stream) {
+    if (!h) return GD_ERR_INVALID_ARG;
+    if (!h->d_state) return fail(h, GD_ERR_INVALID_ARG, "gd_severity: no state bound");
+    if (!d_node_slowdown || !d_node_tier)
+        return fail(h, GD_ERR_INVALID_ARG, "gd_severity: null output");
+    if (T > 0 && (!d_x || !d_med)) return fail(h, GD_ERR_INVALID_ARG, "gd_severity: null input");
+    if (((uintptr_t)d_x & 3) || ((uintptr_t)d_med & 3) || ((uintptr_t)d_node_slowdown & 3))
+        return fail(h, GD_ERR_INVALID_ARG, "gd_severity: misaligned pointer");
+    if (!(moderate <= severe)) return fail(h, GD_ERR_INVALID_ARG, "gd_severity: moderate must not exceed severe");
+    gd_severity_args a;
+    a.state = h->d_state; a.lay = h->lay; a.x = d_x; a.med = d_med;
+    a.slowdown = d_node_slowdown; a.tier = d_node_tier;
+    a.T = T; a.R = h->cfg.n_ranks; a.M = h->cfg.n_metrics; a.N = h->N;
+    a.W = h->cfg.window; a.K = h->cfg.persist_k; a.primary = h->cfg.primary_metric;
+    a.dir = h->cfg.direction[h->cfg.primary_metric];
+    a.moderate = moderate; a.severe = severe;
+    hipError_t e = gd_launch_severity(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(h, e, "gd_severity");
+    return GD_OK;
+}
+
 const char* gd_last_error(gd_handle h) { return h ? h->err.c_str() : g_create_error.c_str(); }
 
 }  // extern "C"

@@ -7,7 +7,7 @@
 #include <stddef.h>
 #include <stdint.h>
 
-// Arguments of the scoring kernel (one workgroup scores one step: all M
+// Arguments of the scoring kernel (a workgroup scores whole steps: all M
 // columns of R ranks, Section 4.2 peer-relative evaluation).
 struct gd_score_args {
     const float* x;        // [T][M][R]
@@ -69,7 +69,20 @@ struct gd_topk_args {
     uint32_t N, k;
 };
 
+struct gd_severity_args {
+    const uint8_t* state;
+    gd_state_layout lay;
+    const float* x;     // [T][M][R]
+    const float* med;   // [T][M]
+    float* slowdown;    // [N]
+    uint8_t* tier;      // [N]
+    uint32_t T, R, M, N, W, K, primary;
+    int32_t dir;        // direction of the primary metric
+    float moderate, severe;
+};
+
 hipError_t gd_launch_score(const gd_score_args& a, hipStream_t s);
+hipError_t gd_launch_severity(const gd_severity_args& a, hipStream_t s);
 hipError_t gd_launch_window(const gd_window_args& a, hipStream_t s);
 hipError_t gd_launch_flags(const gd_flags_args& a, hipStream_t s);
 hipError_t gd_launch_topk(const gd_topk_args& a, hipStream_t s);

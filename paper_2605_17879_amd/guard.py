@@ -22,7 +22,8 @@ NODE_SUM_SCALED = 0
 NODE_MAX = 1
 
 EXPORTS = ("gd_default_config", "gd_create", "gd_destroy", "gd_state_bytes", "gd_bind_state",
-           "gd_score_batch", "gd_update_window", "gd_flags", "gd_topk_nodes", "gd_last_error")
+           "gd_score_batch", "gd_update_window", "gd_flags", "gd_topk_nodes", "gd_severity",
+           "gd_last_error")
 
 
 class GuardError(RuntimeError):
@@ -75,6 +76,8 @@ def load_library() -> ctypes.CDLL:
     lib.gd_flags.restype = ctypes.c_int
     lib.gd_topk_nodes.argtypes = [vp, u32, vp, vp, vp]
     lib.gd_topk_nodes.restype = ctypes.c_int
+    lib.gd_severity.argtypes = [vp, vp, u32, vp, ctypes.c_float, ctypes.c_float, vp, vp, vp]
+    lib.gd_severity.restype = ctypes.c_int
     lib.gd_last_error.argtypes = [vp]
     lib.gd_last_error.restype = ctypes.c_char_p
     _lib = lib
@@ -212,6 +215,19 @@ class Detector:
                                       _p(f.get("rank_first")), _p(f.get("node_flag")),
                                       _p(f.get("node_count")), _p(f.get("node_first")),
                                       self._stream(stream)))
+
+    def alloc_severity(self) -> dict:
+        torch, d = self._torch, self.device
+        return dict(slowdown=torch.empty(self.N, dtype=torch.float32, device=d),
+                    tier=torch.empty(self.N, dtype=torch.uint8, device=d))
+
+    def severity(self, x, out: dict, sev: dict, moderate: float = 0.10, severe: float = 0.20,
+                 stream=None):
+        """Tiers of the flagged nodes from the batch x that `out` was scored from."""
+        T = x.shape[0]
+        assert x.is_cuda and x.is_contiguous() and tuple(x.shape) == (T, self.M, self.R)
+        self._check(self.lib.gd_severity(self.h, x.data_ptr(), T, _p(out["med"]), moderate, severe,
+                                         _p(sev["slowdown"]), _p(sev["tier"]), self._stream(stream)))
 
     def alloc_topk(self, k: int) -> dict:
         torch, d = self._torch, self.device

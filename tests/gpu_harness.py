@@ -93,6 +93,25 @@ def gpu_topk(det: Detector, k: int):
     return tk["idx"].cpu().numpy(), tk["key"].cpu().numpy().view(np.uint64)
 
 
+def compare_severity(p: oracle.Params, d: dict, det: Detector, x: torch.Tensor, out: dict,
+                     moderate=0.10, severe=0.20, label="") -> dict:
+    """gd_severity on the batch x (scored into `out`, window already updated) against the
+    oracle's tiers computed from ITS medians and flags (d = oracle.detect of the same history)."""
+    xd = x.cuda() if not x.is_cuda else x
+    sev = det.alloc_severity()
+    for v in sev.values():
+        v.view(torch.uint8).fill_(0xA5)
+    det.severity(xd, out, sev, moderate, severe)
+    torch.cuda.synchronize()
+    T = x.shape[0]
+    med = d["scores"].med[-T:] if T else d["scores"].med[:0]
+    want_slow, want_tier = oracle.severity(p, x.cpu().numpy(), med, d["node_flag_byte"], moderate, severe)
+    slow, tier = sev["slowdown"].cpu().numpy(), sev["tier"].cpu().numpy()
+    assert np.array_equal(tier, want_tier), f"{label}: tiers differ"
+    assert np.array_equal(bits32(slow), bits32(want_slow)), f"{label}: slowdowns differ"
+    return {"tiers": np.bincount(want_tier, minlength=4).tolist()}
+
+
 def compare_decision(p: oracle.Params, d: dict, det: Detector, topk_k: int, label=""):
     """d = oracle.detect(...) over the whole history the detector has consumed."""
     f = gpu_flags(det)

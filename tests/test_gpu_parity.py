@@ -5,8 +5,8 @@ import pytest
 import torch
 
 import oracle
-from gpu_harness import (compare_decision, compare_scores, detector_for, gpu_score, oracle_params,
-                         run_and_compare)
+from gpu_harness import (compare_decision, compare_scores, compare_severity, detector_for, gpu_score,
+                         oracle_params, run_and_compare)
 from workloads import adversarial, generate, workload
 from workloads.telemetry import ADVERSARIAL_KINDS
 
@@ -221,6 +221,51 @@ def test_topk_request_sizes(R):
     det.close()
 
 
+@pytest.mark.parametrize("R,M,W,T,direction", [(64, 1, 4, 9, 1), (1024, 3, 16, 40, -1),
+                                                  (4096, 2, 1024, 1100, 0), (65536, 2, 6, 5, 1)])
+def test_severity_tiers(R, M, W, T, direction):
+    """Slowdown and tier of every flagged node, bit for bit, for windows from 4 to the
+    longest (1024 steps), histories shorter and longer than the window, each direction."""
+    say(f"case severity R={R} M={M} W={W} T={T} dir={direction}")
+    g = torch.Generator().manual_seed(R + W)
+    x = torch.exp(0.02 * torch.randn((T, M, R), generator=g, dtype=torch.float64))
+    prim = M - 1
+    f = 1.0 if direction >= 0 else -1.0
+    N = R // 8
+    # nodes slowed by 4% .. 32% in the primary metric from the first step on, one of them
+    # only in a single GPU, one only during the first third of the history
+    if N > 8:
+        for i, s in enumerate((1.04, 1.09, 1.12, 1.19, 1.21, 1.32)):
+            x[:, :, ((i * 5 + 1) % N) * 8:((i * 5 + 1) % N) * 8 + 8] *= s ** f
+        x[:, :, ((31 % N) * 8 + 3)] *= 1.25 ** f
+        x[: T // 3, :, (37 % N) * 8:(37 % N) * 8 + 8] *= 1.5 ** f
+    else:                                   # 8 nodes: slow two of them only
+        x[:, :, 8:16] *= 1.12 ** f
+        x[:, :, 48:56] *= 1.32 ** f
+    x = x.to(torch.float32)
+    dirs = tuple(direction for _ in range(M))
+    p = oracle_params(R=R, M=M, W=W, k=max(1, min(W, T) // 2), primary=prim, directions=dirs,
+                      min_signals=1)
+    d = oracle.detect(p, x.numpy(), topk_k=1)
+    det = detector_for(p)
+    out = gpu_score(det, x, want_z=False)
+    det.update_window(out, T)
+    rep = compare_severity(p, d, det, x, out, label="default tiers")
+    say("  nodes per tier", rep)
+    assert sum(rep["tiers"][1:]) >= (3 if N > 8 else 2)
+    compare_severity(p, d, det, x, out, moderate=0.05, severe=0.05, label="one threshold")
+    # the last steps alone (a batch shorter than the window)
+    tail = min(T, 3)
+    sev = det.alloc_severity()
+    out_tail = {k: (v[T - tail:].contiguous() if v is not None else None) for k, v in out.items()}
+    det.severity(x[T - tail:].cuda(), out_tail, sev)
+    torch.cuda.synchronize()
+    want = oracle.severity(p, x[T - tail:].numpy(), d["scores"].med[T - tail:], d["node_flag_byte"])
+    assert np.array_equal(sev["tier"].cpu().numpy(), want[1])
+    assert np.array_equal(sev["slowdown"].cpu().numpy().view(np.uint32), want[0].view(np.uint32))
+    det.close()
+
+
 def _full_size_case(w, seed, chunk, min_flagged_nodes):
     """Score the whole workload in ONE gd_score_batch call on GPU-generated data,
     then window / flags / top-k.  The oracle scores every step of the same bytes
@@ -233,23 +278,31 @@ def _full_size_case(w, seed, chunk, min_flagged_nodes):
     det.score_batch(x, out)
     det.update_window(out, w.T)
     torch.cuda.synchronize()
-    ra, na, near = [], [], [0, 0]
+    ra, na, meds, near = [], [], [], [0, 0]
     last_node_z = None
     for t0 in range(0, w.T, chunk):
         t1 = min(w.T, t0 + chunk)
         o = oracle.score(p, x[t0:t1].cpu().numpy(), want_z=False)
         g = {k: (v[t0:t1] if v is not None else None) for k, v in out.items()}
         compare_scores(o, g, f"steps [{t0},{t1})")
-        ra.append(o.rank_anom); na.append(o.node_anom)
+        ra.append(o.rank_anom); na.append(o.node_anom); meds.append(o.med)
         near[0] += o.near_rank; near[1] += o.near_node
         last_node_z = o.node_z[-1]
         say(f"  steps [{t0},{t1}) match")
-    del x
     pr = oracle.window(p.R, np.concatenate(ra), p.W, p.k)
     pn = oracle.window(p.N, np.concatenate(na), p.W, p.k)
     d = dict(ranks=pr, nodes=pn, node_flag_byte=oracle.node_flag_byte(p.G, pn.flag, pr.flag))
     d["topk_idx"], d["topk_key"] = oracle.topk(pn.count, last_node_z, w.topk)
     compare_decision(p, d, det, w.topk, label="full-size decision")
+    # severity of the flagged nodes over the last W steps of the resident batch
+    sev = det.alloc_severity()
+    det.severity(x, out, sev)
+    torch.cuda.synchronize()
+    want = oracle.severity(p, x[w.T - p.W:].cpu().numpy(), np.concatenate(meds)[w.T - p.W:],
+                           d["node_flag_byte"])
+    assert np.array_equal(sev["tier"].cpu().numpy(), want[1]), "full-size tiers"
+    assert np.array_equal(sev["slowdown"].cpu().numpy().view(np.uint32), want[0].view(np.uint32))
+    say("  nodes per tier", np.bincount(want[1], minlength=4).tolist())
     say("  near-threshold comparisons (rank, node):", near, "flagged ranks", int(pr.flag.sum()),
         "flagged nodes", int(pn.flag.sum()))
     assert int(pn.flag.sum()) >= min_flagged_nodes
