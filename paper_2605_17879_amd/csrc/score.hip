@@ -3,17 +3,21 @@
 // (Section 4.2 peer-relative evaluation and multi-signal rule; Section 7.1
 // 8-GPU nodes).
 //
-// One workgroup scores one step.  For each of the step's M columns it
-//   1. loads the column once from HBM into registers (float4 per lane per row,
-//      coalesced, rank-contiguous) -- the column is never read again;
-//   2. finds the two middle order statistics by counting: a sample taken from
-//      the first-arriving registers brackets the median, one pass puts the
-//      bracketed values into an LDS histogram of order-preserving integer keys,
-//      a scan locates the bucket(s) holding the wanted ranks, a second pass
+// Persistent workgroups: each takes a contiguous run of steps and scores them
+// column after column.  For each of a step's M columns it
+//   1. holds the column in registers (float4 per lane per row, loaded once from
+//      HBM, coalesced, rank-contiguous; the next column is loaded row by row
+//      while the current one is scored) -- a column is never read again;
+//   2. finds the two middle order statistics by counting: a bracket (taken from
+//      the previous step of the same metric, else from a sample of the column)
+//      is counted into an LDS histogram of order-preserving integer keys, a
+//      scan locates the bucket(s) holding the wanted ranks, a second pass
 //      gathers that bucket's few values into LDS where they are ranked exactly;
 //      a bracket that misses, or a bucket that is too full (ties), falls back
 //      to wider or narrower ranges until the answer is exact;
-//   3. does the same for |x - med| to get the MAD;
+//   3. gets the MAD from the same histogram (pairs of bucket edges around the
+//      median bound the wanted distances; one pass counts and gathers), or by a
+//      second selection on |x - med| when that does not apply;
 //   4. computes z, the exceedance bits and the node scores from the registers.
 // After the M columns the per-rank mask bytes, anomaly bits and node outputs
 // are written.  HBM traffic is the 4 bytes per sample read plus ~1.8 bytes per
@@ -398,12 +402,17 @@ __device__ __forceinline__ bool block_select(SH& sh, const Keys& keys, uint32_t 
             const uint32_t tok = keys.token();
 #pragma unroll
             for (int j = 0; j < ROWS; ++j) {
+                // one test per register row (hits are rare): the smallest offset decides
+                uint32_t off[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const uint32_t kk = keys.at(j, i, tok);
-                    if (kk - clo <= cspan) {
-                        uint32_t pos = atomicAdd(&sh.ncand, 1u);
-                        if (pos < (uint32_t)CAND_CAP) sh.cand[pos] = kk;
+                for (int i = 0; i < 4; ++i) off[i] = keys.at(j, i, tok) - clo;
+                if (min(min(off[0], off[1]), min(off[2], off[3])) <= cspan) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        if (off[i] <= cspan) {
+                            uint32_t pos = atomicAdd(&sh.ncand, 1u);
+                            if (pos < (uint32_t)CAND_CAP) sh.cand[pos] = off[i] + clo;
+                        }
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -543,13 +552,21 @@ __device__ __forceinline__ bool mad_from_histogram(SH& sh, const float (&v)[ROWS
         const uint32_t tok = opaque_s(__float_as_uint(med));
 #pragma unroll
         for (int j = 0; j < ROWS; ++j) {
+            uint32_t off[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const uint32_t kk = __float_as_uint(fabsf(v[j][i] - __uint_as_float(tok)));
                 nbelow += kk < d1 ? 1u : 0u;
-                if (kk - d1 <= span) {
-                    uint32_t pos = atomicAdd(&sh.ncand, 1u);
-                    if (pos < (uint32_t)CAND_CAP) sh.cand[pos] = kk;
+                off[i] = kk - d1;
+            }
+            // one test per register row (hits are rare): the smallest offset decides
+            if (min(min(off[0], off[1]), min(off[2], off[3])) <= span) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (off[i] <= span) {
+                        uint32_t pos = atomicAdd(&sh.ncand, 1u);
+                        if (pos < (uint32_t)CAND_CAP) sh.cand[pos] = off[i] + d1;
+                    }
                 }
             }
             asm volatile("" : "+v"(nbelow));
