@@ -234,20 +234,20 @@ __device__ __forceinline__ bool locate(SH& sh, uint32_t tid, uint32_t ka, uint32
 // Exact ranking of the cnt gathered candidates in sh.cand (ties broken by
 // position): the candidates of rank wa and wb go to sh.res[4] and sh.res[5].
 // Each wave takes every (NT/64)-th candidate; its lanes split the comparisons
-// and add their counts up across the wave.  Ends with a barrier.
+// and the wave counts the lanes that answered yes.  Ends with a barrier.
 template <int NT, typename SH>
 __device__ __forceinline__ void rank_candidates(SH& sh, uint32_t tid, uint32_t cnt, uint32_t wa,
                                                 uint32_t wb) {
     const uint32_t lane = tid & (WAVE - 1), w = rfl(tid >> 6);
     for (uint32_t i = w; i < cnt; i += NT / WAVE) {
         const uint32_t c = sh.cand[i];
-        uint32_t r = 0;
-        for (uint32_t j = lane; j < cnt; j += WAVE) {
-            const uint32_t cj = sh.cand[j];
-            r += (cj < c || (cj == c && j < i)) ? 1u : 0u;
+        uint32_t r = 0;                      // wave-uniform: candidates ordered before candidate i
+        for (uint32_t j0 = 0; j0 < cnt; j0 += WAVE) {
+            const uint32_t j = j0 + lane;
+            const uint32_t cj = j < cnt ? sh.cand[j] : 0xFFFFFFFFu;
+            r += (uint32_t)__popcll(__ballot(j < cnt && (cj < c || (cj == c && j < i))));
         }
-        r = wave_incl_scan(r);
-        if (lane == WAVE - 1) {
+        if (lane == 0) {
             if (r == wa) sh.res[4] = c;
             if (r == wb) sh.res[5] = c;
         }
