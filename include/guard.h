@@ -98,6 +98,17 @@ size_t gd_state_bytes(gd_handle h);
 gd_status gd_bind_state(gd_handle h, void* d_state, size_t state_bytes);
 
 /*
+ * Tuning of gd_score_batch for short batches (the streaming case of Section 4.2's
+ * continuous monitoring: one evaluation per call).  A batch of at most max_steps
+ * steps whose columns fit the chip side by side is scored with one workgroup per
+ * (step, metric) column instead of one per run of steps; the results are the same
+ * bit for bit, only the latency of a call differs.  0 switches this off.  The
+ * default is GD_DEFAULT_STREAMING_STEPS.
+ */
+#define GD_DEFAULT_STREAMING_STEPS 4u
+gd_status gd_set_streaming_steps(gd_handle h, uint32_t max_steps);
+
+/*
  * Score T steps (Section 4.2: peer-relative evaluation, multi-signal rule with
  * step time primary; Section 7.1: 8-GPU nodes).  With N = R/8, RW = ceil(R/64),
  * NW = ceil(N/64):

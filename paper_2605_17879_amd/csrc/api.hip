@@ -16,6 +16,7 @@ struct gd_handle_s {
     uint32_t N, RW, NW;
     gd_state_layout lay;
     uint8_t* d_state;
+    uint32_t split_steps;
     std::string err;
 };
 
@@ -115,12 +116,19 @@ gd_status gd_create(const gd_config* c, gd_handle* out) {
     h->NW = (N + 63) / 64;
     h->lay = make_layout(c->n_ranks, N, c->window);
     h->d_state = nullptr;
+    h->split_steps = GD_DEFAULT_STREAMING_STEPS;
     *out = h;
     return GD_OK;
 }
 
 gd_status gd_destroy(gd_handle h) {
     delete h;
+    return GD_OK;
+}
+
+gd_status gd_set_streaming_steps(gd_handle h, uint32_t max_steps) {
+    if (!h) return GD_ERR_INVALID_ARG;
+    h->split_steps = max_steps;
     return GD_OK;
 }
 
@@ -158,6 +166,7 @@ gd_status gd_score_batch(gd_handle h, const float* d_x, uint32_t T, float* d_med
     a.T = T; a.R = h->cfg.n_ranks; a.M = h->cfg.n_metrics; a.N = h->N;
     a.primary = h->cfg.primary_metric; a.min_signals = h->cfg.min_signals;
     a.node_agg = h->cfg.node_agg;
+    a.split_steps = h->split_steps;
     a.thr = h->cfg.z_threshold; a.node_scale = h->cfg.node_scale;
     a.rel_floor = h->cfg.rel_floor; a.abs_floor = h->cfg.abs_floor;
     memcpy(a.dir, h->cfg.direction, 8);

@@ -21,6 +21,7 @@ struct gd_score_args {
     uint64_t* node_anom;   // [T][NW]
     uint32_t T, R, M, N;
     uint32_t primary, min_signals, node_agg;
+    uint32_t split_steps;  // batches of at most this many steps take one workgroup per column
     float thr, node_scale, rel_floor, abs_floor;
     int8_t dir[8];
 };

@@ -679,7 +679,11 @@ __device__ __forceinline__ void score_row_decide(const float (&x)[4], float xsta
 }
 
 // FULL: R == NT*4*ROWS exactly, so no lane is padding and no bounds are checked.
-template <int NT, int ROWS, int LOG_NB, bool FULL>
+// SPLIT (short batches, the streaming case): one workgroup per column instead of
+// per run of steps, so that the M columns of a step are scored side by side.  The
+// exceed bits of a column are then OR-ed into the (zeroed) mask outputs in global
+// memory and combine_kernel applies the multi-signal rule afterwards.
+template <int NT, int ROWS, int LOG_NB, bool FULL, bool SPLIT>
 __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
     constexpr int BLK = NT * 4;               // ranks per register row
     constexpr int MAX_NODES = BLK * ROWS / 8;
@@ -698,10 +702,11 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
     const float thr = a.thr;
     // Each workgroup scores a contiguous run of steps, column after column, and
     // loads the next column while it scores the current one.
-    const uint32_t spw = (a.T + gridDim.x - 1) / gridDim.x;
-    const uint32_t t_begin = blockIdx.x * spw;
+    const uint32_t spw = SPLIT ? 1u : (a.T + gridDim.x - 1) / gridDim.x;
+    const uint32_t t_begin = SPLIT ? blockIdx.x / M : blockIdx.x * spw;
     const uint32_t t_end = min(a.T, t_begin + spw);
     if (t_begin >= t_end) return;
+    const uint32_t m_begin = SPLIT ? blockIdx.x % M : 0u, m_end = SPLIT ? m_begin + 1u : M;
 
     // Row j of wave w covers rank block (j + w) % ROWS, so that the first
     // registers to arrive (row 0) sample the whole rank range.
@@ -752,7 +757,7 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
     };
     {
         const uint32_t tl = fresh_tid4();
-        const float* col = a.x + (size_t)t_begin * M * R;
+        const float* col = a.x + ((size_t)t_begin * M + m_begin) * R;
         // issued in row order, like the refills of the score loop: the waits of the
         // first pass over a column are then placed row by row
 #pragma unroll
@@ -767,11 +772,11 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
     for (int j = 0; j < ROWS; ++j) emask[j * NT + tid] = 0;   // each slot is private to its thread
 #pragma unroll
     for (int j = 0; j < (ROWS + 3) / 4; ++j) NE[j] = 0;
-    for (uint32_t m = 0; m < M; ++m) {
+    for (uint32_t m = m_begin; m < m_end; ++m) {
         // the column after this one (next metric, or the next step's first metric)
         // (after the very last column the current one is simply read again: a
         // branch-free refill keeps the register allocation of the score loops simple)
-        const bool have_next = m + 1 < M || t + 1 < t_end;
+        const bool have_next = !SPLIT && (m + 1 < M || t + 1 < t_end);
         const float* next_col = a.x + (t * M + m + (have_next ? 1 : 0)) * (size_t)R;
         const uint32_t tl = fresh_tid4();
         const bool svalid = FULL || rbase(0, tl) < R;
@@ -952,16 +957,33 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
                                   __HIP_MEMORY_SCOPE_WORKGROUP);
             NE[j / 4] |= (nz > thr ? 1u : 0u) << (8 * (j & 3) + m);
             if (prim && (FULL || rbase(j, tz) < R) && !(tz & 4)) nzrow[rbase(j, tz) / 8] = nz;
-            load_row(j, next_col, tz);      // the row is done: refill it with the next column
+            if (!SPLIT) load_row(j, next_col, tz);   // the row is done: refill it with the next column
             // pin the row's results here, or its scores stay live until the loop ends
             asm volatile("" : "+v"(NE[j / 4]));
             __builtin_amdgcn_sched_barrier(0);
         }
     }
 
-    // per-rank mask bytes and anomaly bits
     const uint32_t to = fresh_tid4();
     uint8_t* erow = a.exceed_mask + t * R;
+    if (SPLIT) {
+        // this column's bits join those of the step's other columns in global memory
+        // (R and N are multiples of 4 here, the outputs word-aligned: see the launcher)
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+            if (!(FULL || rbase(j, to) < R)) continue;
+            const uint32_t Ej = emask[j * NT + to / 4];
+            if (Ej) atomicOr(reinterpret_cast<uint32_t*>(erow + rbase(j, to)), Ej);
+            const uint32_t nb = (NE[j / 4] >> (8 * (j & 3))) & 0xFFu;
+            if (nb && !(to & 4)) {
+                const size_t nidx = t * N + rbase(j, to) / 8;
+                atomicOr(reinterpret_cast<uint32_t*>(a.node_mask + (nidx & ~(size_t)3)),
+                         nb << (8 * (uint32_t)(nidx & 3)));
+            }
+        }
+        return;
+    }
+    // per-rank mask bytes and anomaly bits
     uint64_t* arow = a.rank_anom + t * RW;
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
@@ -1004,29 +1026,105 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
     }   // steps of this workgroup
 }
 
+// Split route, before the columns are scored: the mask outputs start at zero.
+// (A fill kernel rather than a memset, so that a caller may capture the call.)
+__global__ __launch_bounds__(256) void zero_masks_kernel(uint32_t* exceed_words, size_t n_exceed,
+                                                         uint32_t* node_words, size_t n_node) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n_exceed) exceed_words[i] = 0;
+    if (i < n_node) node_words[i] = 0;
+}
+
+// Split route, after the columns: the multi-signal rule (primary bit set and at
+// least min_signals bits) on the finished mask bytes.  blockIdx.y = step; a
+// thread takes four ranks (one mask word), 16 lanes make one 64-bit word.
+__global__ __launch_bounds__(256) void combine_kernel(const gd_score_args a) {
+    const uint32_t t = blockIdx.y, lane = threadIdx.x & (WAVE - 1);
+    const uint32_t R = a.R, N = a.N;
+    const uint32_t RW = (R + 63) / 64, NWD = (N + 63) / 64;
+    const uint32_t q = blockIdx.x * 256 + threadIdx.x;          // mask word index in the step
+    if ((q & ~63u) * 4 < R) {                                   // some lane of this wave has ranks
+        const bool valid = q * 4 < R;
+        const uint32_t Ej = valid ? reinterpret_cast<const uint32_t*>(a.exceed_mask + (size_t)t * R)[q] : 0u;
+        const uint32_t prim_set = (Ej >> a.primary) & 0x01010101u;
+        uint32_t pc = Ej - ((Ej >> 1) & 0x55555555u);
+        pc = (pc & 0x33333333u) + ((pc >> 2) & 0x33333333u);
+        pc = (pc + (pc >> 4)) & 0x0F0F0F0Fu;
+        const uint32_t enough = ((pc + (0x80u - a.min_signals) * 0x01010101u) >> 7) & 0x01010101u;
+        const uint32_t an = prim_set & enough;
+        const uint32_t nib = (an | (an >> 7) | (an >> 14) | (an >> 21)) & 0xFu;
+        const uint32_t sub = lane & 15;
+        uint32_t wlo = sub < 8 ? nib << (4 * sub) : 0u;
+        uint32_t whi = sub >= 8 ? nib << (4 * (sub - 8)) : 0u;
+        wlo |= lane_xor<1>(wlo); whi |= lane_xor<1>(whi);
+        wlo |= lane_xor<2>(wlo); whi |= lane_xor<2>(whi);
+        wlo |= lane_xor<4>(wlo); whi |= lane_xor<4>(whi);
+        wlo |= lane_xor<8>(wlo); whi |= lane_xor<8>(whi);
+        if (sub == 0 && valid) a.rank_anom[(size_t)t * RW + q / 16] = ((uint64_t)whi << 32) | wlo;
+    }
+    const uint32_t n = blockIdx.x * 256 + threadIdx.x;
+    if ((n & ~63u) < N) {
+        bool an = false;
+        if (n < N) {
+            const uint32_t b = a.node_mask[(size_t)t * N + n];
+            an = ((b >> a.primary) & 1u) && (uint32_t)__popc(b) >= a.min_signals;
+        }
+        const uint64_t word = __ballot(an);
+        if (lane == 0) a.node_anom[(size_t)t * NWD + n / 64] = word;
+    }
+}
+
+int compute_units(hipError_t* err) {
+    static int n_cu = 0;
+    *err = hipSuccess;
+    if (n_cu == 0) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) { *err = e; return 0; }
+        if (n_cu <= 0) n_cu = 256;
+    }
+    return n_cu;
+}
+
+// One workgroup per column needs whole mask words per step (R, N multiples of 4,
+// word-aligned outputs) and pays off while the columns fit the chip side by side.
+bool use_split(const gd_score_args& a, int n_cu) {
+    return a.split_steps > 0 && a.T <= a.split_steps && (uint64_t)a.T * a.M <= (uint64_t)n_cu &&
+           a.R % 32 == 0 && ((uintptr_t)a.node_mask & 3) == 0;
+}
+
 template <int NT, int ROWS, int LOG_NB, bool FULL>
 hipError_t launch_one(const gd_score_args& a, hipStream_t s) {
     using SH = Shared<NT, LOG_NB, NT * 4 * ROWS / 8>;
     constexpr size_t lds = ((sizeof(SH) + 15) & ~(size_t)15) + (size_t)ROWS * NT * 4;
     static_assert(lds <= 160 * 1024, "LDS budget of one CU");
-    auto kern = score_kernel<NT, ROWS, LOG_NB, FULL>;
+    auto kern = score_kernel<NT, ROWS, LOG_NB, FULL, false>;
+    auto kern_split = score_kernel<NT, ROWS, LOG_NB, FULL, true>;
     static bool configured = false;      // a handle is single-threaded; a repeated set is harmless
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_split),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
+    hipError_t cu_err;
+    const int n_cu = compute_units(&cu_err);
+    if (cu_err != hipSuccess) return cu_err;
+    if (use_split(a, n_cu)) {
+        const size_t n_exceed = (size_t)a.T * a.R / 4, n_node = (size_t)a.T * a.N / 4;
+        hipLaunchKernelGGL(zero_masks_kernel, dim3((uint32_t)((n_exceed + 255) / 256)), dim3(256), 0, s,
+                           reinterpret_cast<uint32_t*>(a.exceed_mask), n_exceed,
+                           reinterpret_cast<uint32_t*>(a.node_mask), n_node);
+        hipLaunchKernelGGL(kern_split, dim3(a.T * a.M), dim3(NT), lds, s, a);
+        hipLaunchKernelGGL(combine_kernel, dim3((a.R / 4 + 255) / 256, a.T), dim3(256), 0, s, a);
+        return hipGetLastError();
+    }
     // Enough workgroups to fill every CU once (as many as fit by LDS and wave
     // slots); each takes a contiguous run of ceil(T / grid) steps.
-    static int n_cu = 0;
-    if (n_cu == 0) {
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess) return e;
-        if (n_cu <= 0) n_cu = 256;
-    }
     const size_t by_lds = (size_t)160 * 1024 / lds, by_waves = (size_t)16 / (NT / WAVE);
     const size_t per_cu = by_lds < by_waves ? (by_lds ? by_lds : 1) : by_waves;
     const size_t cap = (size_t)n_cu * per_cu;

@@ -22,8 +22,8 @@ NODE_SUM_SCALED = 0
 NODE_MAX = 1
 
 EXPORTS = ("gd_default_config", "gd_create", "gd_destroy", "gd_state_bytes", "gd_bind_state",
-           "gd_score_batch", "gd_update_window", "gd_flags", "gd_topk_nodes", "gd_severity",
-           "gd_last_error")
+           "gd_set_streaming_steps", "gd_score_batch", "gd_update_window", "gd_flags",
+           "gd_topk_nodes", "gd_severity", "gd_last_error")
 
 
 class GuardError(RuntimeError):
@@ -68,6 +68,8 @@ def load_library() -> ctypes.CDLL:
     lib.gd_state_bytes.restype = ctypes.c_size_t
     lib.gd_bind_state.argtypes = [vp, vp, ctypes.c_size_t]
     lib.gd_bind_state.restype = ctypes.c_int
+    lib.gd_set_streaming_steps.argtypes = [vp, u32]
+    lib.gd_set_streaming_steps.restype = ctypes.c_int
     lib.gd_score_batch.argtypes = [vp, vp, u32] + [vp] * 9
     lib.gd_score_batch.restype = ctypes.c_int
     lib.gd_update_window.argtypes = [vp, vp, vp, vp, u32, u64, vp]
@@ -171,6 +173,10 @@ class Detector:
     def bind_state(self, state):
         self._check(self.lib.gd_bind_state(self.h, state.data_ptr(), state.numel() * state.element_size()))
         self.state = state
+
+    def set_streaming_steps(self, max_steps: int):
+        """Batches of at most max_steps steps are scored one workgroup per column (0: never)."""
+        self._check(self.lib.gd_set_streaming_steps(self.h, max_steps))
 
     def alloc_outputs(self, T: int, want_z: bool = False) -> dict:
         """Output tensors of gd_score_batch for T steps (plain allocation)."""

@@ -16,6 +16,9 @@ import oracle
 from paper_2605_17879_amd import Config, Detector
 
 Z_RTOL = 1e-6
+# None: the library's own choice between one workgroup per run of steps and one per
+# column; 0: never per column; 64: per column whenever the columns fit the chip.
+STREAMING_STEPS = None
 
 
 def oracle_params(w=None, **kw) -> oracle.Params:
@@ -33,7 +36,10 @@ def detector_for(p: oracle.Params, topk=None) -> Detector:
                  node_agg=p.node_agg, z_threshold=p.thr, node_scale=p.node_scale,
                  rel_floor=p.rel_floor, abs_floor=p.abs_floor,
                  direction=tuple(p.directions)[: p.M])
-    return Detector(cfg)
+    det = Detector(cfg)
+    if STREAMING_STEPS is not None:
+        det.set_streaming_steps(STREAMING_STEPS)
+    return det
 
 
 def u64(t: torch.Tensor) -> np.ndarray:

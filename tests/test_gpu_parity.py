@@ -13,6 +13,17 @@ from workloads.telemetry import ADVERSARIAL_KINDS
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(params=["auto", "per-run", "per-column"])
+def route(request):
+    """Short batches can be scored one workgroup per run of steps or one per column:
+    the cases that use this fixture run through the library's own choice and through
+    each route forced."""
+    import gpu_harness
+    gpu_harness.STREAMING_STEPS = {"auto": None, "per-run": 0, "per-column": 64}[request.param]
+    yield request.param
+    gpu_harness.STREAMING_STEPS = None
+
+
 def say(*a):
     print(*a, flush=True)
 
@@ -23,7 +34,7 @@ SHAPES = [(8, 1), (24, 3), (64, 1), (72, 2), (256, 4), (1000, 2), (1024, 4), (20
 
 
 @pytest.mark.parametrize("R,M", SHAPES)
-def test_shapes_full_and_ragged(R, M):
+def test_shapes_full_and_ragged(R, M, route):
     T = 5 if R <= 16384 else 3
     say(f"case shapes R={R} M={M} T={T}")
     g = torch.Generator().manual_seed(R * 31 + M)
@@ -41,7 +52,7 @@ def test_shapes_full_and_ragged(R, M):
 
 @pytest.mark.parametrize("kind", ADVERSARIAL_KINDS)
 @pytest.mark.parametrize("R", [64, 4096, 65536])
-def test_adversarial_columns(kind, R):
+def test_adversarial_columns(kind, R, route):
     T, M = (4, 2) if R < 65536 else (2, 2)
     say(f"case adversarial kind={kind} R={R}")
     x = adversarial(kind, R, T, M, seed=R % 97)
@@ -53,7 +64,7 @@ def test_adversarial_columns(kind, R):
 
 @pytest.mark.parametrize("agg", [oracle.NODE_SUM_SCALED, oracle.NODE_MAX])
 @pytest.mark.parametrize("R", [1024, 16384])
-def test_node_aggregation_rules_and_options(agg, R):
+def test_node_aggregation_rules_and_options(agg, R, route):
     say(f"case node_agg={agg} R={R}")
     g = torch.Generator().manual_seed(5)
     x = torch.exp(0.02 * torch.randn((6, 3, R), generator=g, dtype=torch.float64)).to(torch.float32)
@@ -65,7 +76,7 @@ def test_node_aggregation_rules_and_options(agg, R):
 
 
 @pytest.mark.parametrize("thr", [0.0, -0.75, 1e-3, 2.0, 30.0])
-def test_thresholds_that_crowd_the_decision_boundary(thr):
+def test_thresholds_that_crowd_the_decision_boundary(thr, route):
     """With the threshold inside the bulk of the node scores many estimated node
     scores fall within the rounding margin and must be settled exactly."""
     R, M, T = 65536, 4, 3
@@ -81,7 +92,7 @@ def test_thresholds_that_crowd_the_decision_boundary(thr):
     assert rep["z_bit_exact"]
 
 
-def test_tiny_configuration():
+def test_tiny_configuration(route):
     w = workload(0)
     say("case", w.name)
     x = generate(w, seed=0)
@@ -118,7 +129,7 @@ def test_configuration_3_prefix_with_window_wrap():
     say("  report", rep)
 
 
-def test_streaming_configuration_prefix():
+def test_streaming_configuration_prefix(route):
     """Config 4's launch shape: one step per call, ring kept on the device."""
     w = workload(4, T=300, W=64, k=48)
     say("case", w.name, "300 single-step calls, W=64")
