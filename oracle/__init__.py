@@ -12,7 +12,9 @@ on tiny columns, ``numpy.median`` on float32, closed forms on ramps, a worked
 stragglers injected with a constructed margin, spike immunity, brute-force
 top-k; for the severity tiers: exact rational arithmetic on small cases,
 ``numpy.median`` of the quotients, constructed slowdowns, the window's extent,
-both directions, tier boundaries.  No function here is "parity unpinned".
+both directions, tier boundaries; for missing samples (NaN): ``numpy.nanmedian``,
+exact rational arithmetic, and the same cluster without its silent nodes.  No
+function here is "parity unpinned".
 """
 from __future__ import annotations
 

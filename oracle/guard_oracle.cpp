@@ -132,12 +132,21 @@ void go_score(const go_config* c, const float* x, uint64_t T, float* med, float*
         for (size_t m = 0; m < M; ++m) {
             const float* xc = x + ((size_t)t * M + m) * R;
             for (size_t r = 0; r < R; ++r) col[r] = canon(xc[r]);
-            // peer baseline: median over the ranks of this step and metric
-            work = col;
-            const float md = median_by_sort(work);
+            // Rule "missing": a NaN is a sample that did not arrive.  It is left out of
+            // the column's median and MAD (taken over the samples present), scores
+            // z = 0, never exceeds and adds 0 to its node's score.  A column with no
+            // sample present has med = MAD = NaN and nobody exceeds.
+            // peer baseline: median over the ranks present in this step and metric
+            work.clear();
+            for (size_t r = 0; r < R; ++r)
+                if (!std::isnan(col[r])) work.push_back(col[r]);
+            const bool any_present = !work.empty();
+            const float md = any_present ? median_by_sort(work) : std::nanf("");
             // spread: median of absolute deviations from that median
-            for (size_t r = 0; r < R; ++r) work[r] = std::fabs(col[r] - md);
-            const float ma = median_by_sort(work);
+            work.clear();
+            for (size_t r = 0; r < R; ++r)
+                if (!std::isnan(col[r])) work.push_back(std::fabs(col[r] - md));
+            const float ma = any_present ? median_by_sort(work) : std::nanf("");
             med[(size_t)t * M + m] = md;
             mad[(size_t)t * M + m] = ma;
             // scale with floors, so that a column with MAD = 0 stays finite
@@ -147,6 +156,11 @@ void go_score(const go_config* c, const float* x, uint64_t T, float* med, float*
             s = std::max(s, c->abs_floor);
             const int dir = c->direction[m];
             for (size_t r = 0; r < R; ++r) {
+                if (std::isnan(col[r])) {           // missing
+                    if (z) z[((size_t)t * M + m) * R + r] = 0.0f;
+                    zs[r] = 0.0f;
+                    continue;
+                }
                 float d = col[r] - md;
                 float zr = d / s;
                 if (z) z[((size_t)t * M + m) * R + r] = zr;
