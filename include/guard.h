@@ -128,7 +128,14 @@ gd_status gd_set_streaming_steps(gd_handle h, uint32_t max_steps);
  *
  * All arithmetic is IEEE fp32, one rounding per operation, -0 read as +0.
  * T == 0 is a valid no-op.  Every output except d_z is required.
- */
+  *
+ * Missing samples: a NaN in d_x is a sample that did not arrive (polled telemetry
+ * does not always answer, Section 7.1).  It is left out of its column's median and
+ * MAD, which are taken over the samples present (the middle one of an odd number);
+ * its z is 0, it never exceeds and it adds 0 to its node's score.  A column with
+ * no sample present reports med = MAD = NaN and no exceedance.  Infinities remain
+ * unsupported input (no fault; that column's results are unspecified).
+*/
 gd_status gd_score_batch(gd_handle h, const float* d_x, uint32_t T, float* d_med, float* d_mad,
                          float* d_z, uint8_t* d_exceed_mask, uint64_t* d_rank_anom,
                          float* d_node_z, uint8_t* d_node_mask, uint64_t* d_node_anom,
@@ -193,7 +200,9 @@ gd_status gd_topk_nodes(gd_handle h, uint32_t k, int32_t* d_idx, uint64_t* d_key
  *   d_node_tier     [N] u8  device: 0 not flagged; 1 slowdown < moderate;
  *                            2 moderate <= slowdown < severe; 3 slowdown >= severe
  * moderate > severe is GD_ERR_INVALID_ARG.  T == 0 reports tier 0 everywhere.
- * Zero or non-finite medians or samples give an unspecified slowdown for that node.
+ * Missing samples (NaN) and steps whose median is NaN are left out of the quotients;
+ * a flagged node with none left reports slowdown 0 in tier 1.  Zero medians or
+ * samples and infinities give an unspecified slowdown for that node.
  */
 gd_status gd_severity(gd_handle h, const float* d_x, uint32_t T, const float* d_med, float moderate,
                       float severe, float* d_node_slowdown, uint8_t* d_node_tier, void* stream);

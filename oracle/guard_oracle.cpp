@@ -285,6 +285,8 @@ void go_topk(uint32_t N, const uint16_t* node_count, const float* node_z_last, u
 // a lower-is-worse primary divides the other way round, a two-sided one takes
 // whichever quotient is >= 1.  The node's slowdown is the median of those
 // min(T, W) * G quotients (rule "median") minus 1, each operation rounded to fp32.
+// Missing samples (NaN, rule "missing") and steps whose median is NaN are left out;
+// a flagged node with no quotient at all reports slowdown 0 in tier 1.
 //   tier 0: node_flag_byte[n] == 0 (not flagged; slowdown reported as 0)
 //   tier 1: flagged, slowdown <  moderate           ("pending verification")
 //   tier 2: flagged, moderate <= slowdown < severe  (mitigate at next checkpoint)
@@ -305,12 +307,17 @@ void go_severity(const go_config* c, const float* x, uint64_t T, const float* me
             const float m = med[t * M + p];
             for (uint32_t g = 0; g < G; ++g) {
                 const float xv = canon(x[(t * M + p) * (uint64_t)R + (uint64_t)n * G + g]);
+                if (std::isnan(xv) || std::isnan(m)) continue;     // rule "missing": left out
                 float r;
                 if (dir > 0) r = xv / m;
                 else if (dir < 0) r = m / xv;
                 else r = xv >= m ? xv / m : m / xv;
                 q.push_back(r);
             }
+        }
+        if (q.empty()) {            // flagged, but nothing arrived inside the window
+            tier[n] = 1;
+            continue;
         }
         const float s = median_by_sort(q) - 1.0f;
         slowdown[n] = s;

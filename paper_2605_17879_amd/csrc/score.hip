@@ -155,8 +155,10 @@ struct XKeys {
         if (PLAIN) return __float_as_uint(f);
         // -0 reads as +0; the zero is derived from the opaque token so that the
         // sum is recomputed per pass instead of being kept for all 64 values
-        const uint32_t b = __float_as_uint(f + __uint_as_float(tok - 31u));
-        return b ^ ((uint32_t)((int32_t)b >> tok) | 0x80000000u);   // tok is an opaque 31
+        const float g = f + __uint_as_float(tok - 31u);
+        const uint32_t b = __float_as_uint(g);
+        const uint32_t k = b ^ ((uint32_t)((int32_t)b >> tok) | 0x80000000u);   // tok is an opaque 31
+        return g != g ? 0xFFFFFFFFu : k;     // a missing sample (NaN) lies above every value
     }
     __device__ __forceinline__ uint32_t at(int j, int i, uint32_t tok) const { return key(v[j][i], tok); }
     __device__ __forceinline__ float value(uint32_t k) const {
@@ -282,8 +284,9 @@ __device__ __forceinline__ int shift_for(uint32_t span) {
 //
 // umax_slot (with a handed-in bracket only): the first counting pass also finds the
 // largest raw bit pattern of the column and leaves it in *umax_out.  Should it carry
-// a sign bit, the raw bits were no valid keys: the selection stops after clearing
-// its work area and the caller starts over with order-preserving keys.
+// a sign bit or be a NaN's, the raw bits were no valid keys or the ranks asked for
+// not the right ones: the selection stops after clearing its work area and the
+// caller starts over.
 template <int NT, int ROWS, int LOG_NB, bool WIDE, typename SH, typename Keys>
 __device__ __forceinline__ bool block_select(SH& sh, const Keys& keys, uint32_t skey, bool svalid,
                                              uint32_t n, uint32_t k0, uint32_t k1, uint32_t* out0,
@@ -315,11 +318,14 @@ __device__ __forceinline__ bool block_select(SH& sh, const Keys& keys, uint32_t 
         const uint32_t ra = half > delta ? half - 1 - delta : 0u;
         const uint32_t rb = min(n - 1, half + delta);
         uint32_t unused;
-        (void)locate<NT, LOG_NB, false, false>(sh, tid, ra, rb, &unused);
+        const bool both = locate<NT, LOG_NB, false, false>(sh, tid, ra, rb, &unused);
         const uint32_t ba = rfl(sh.res[0]), bb = rfl(sh.res[2]);
         lo = ra == 0 ? 0u : smin + (ba << sshift);
         const uint64_t hend = (uint64_t)smin + ((uint64_t)(bb + 1) << sshift) - 1;
         hi = rb == n - 1 ? 0xFFFFFFFFu : (hend > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)hend);
+        // Fewer samples than n went in when some were missing values: a sample rank
+        // beyond them was not located, and the bracket is then left open.
+        if (!both) { lo = 0; hi = 0xFFFFFFFFu; }
     };
     if (!hinted) sample_bracket();
     // mode 0: both statistics together; 1: k0 alone; 2: k1 alone (after a split)
@@ -372,7 +378,7 @@ __device__ __forceinline__ bool block_select(SH& sh, const Keys& keys, uint32_t 
         if (with_umax) {
             const uint32_t umax = rfl(*umax_slot);
             *umax_out = umax;
-            if (umax >= 0x80000000u) {
+            if (umax > 0x7F800000u) {
                 uint32_t unused;
                 (void)locate<NT, LOG_NB, false, true>(sh, tid, ka, kb, &unused);   // clears the work area
                 *out0 = 0; *out1 = 0;
@@ -592,20 +598,23 @@ __device__ __forceinline__ bool mad_from_histogram(SH& sh, const float (&v)[ROWS
 }
 
 // Signed score and node score of one register row, dividing with the IEEE
-// operator.  AGG 0 = scaled pairwise sum, 1 = max.
+// operator.  AGG 0 = scaled pairwise sum, 1 = max.  This is the route of every
+// column that holds a missing sample.
 template <int AGG>
 __device__ __forceinline__ void score_row(const float (&x)[4], float med, float s, uint32_t absmask,
                                           uint32_t sgnmask, float thr, float node_scale,
                                           uint32_t* e, float* nz) {
     float zs[4];
+    uint32_t bits = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const float z = ((x[i] + 0.0f) - med) / s;      // -0 reads as +0
-        zs[i] = __uint_as_float((__float_as_uint(z) & absmask) ^ sgnmask);
+        const float zi = __uint_as_float((__float_as_uint(z) & absmask) ^ sgnmask);
+        // A NaN is a missing sample and its score a NaN: it never exceeds (the
+        // comparison is false) and adds nothing to its node.
+        bits |= (zi > thr ? 1u : 0u) << (8 * i);
+        zs[i] = zi == zi ? zi : 0.0f;
     }
-    uint32_t bits = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) bits |= (zs[i] > thr ? 1u : 0u) << (8 * i);
     *e = bits;
     // lanes 2p and 2p+1 hold GPUs 0-3 and 4-7 of one node
     if (AGG == 0) {
@@ -739,7 +748,7 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
         __syncthreads();
     }
 
-    const uint32_t k0 = R / 2 - 1, k1 = R / 2;   // R is even
+    const uint32_t k0_all = R / 2 - 1, k1_all = R / 2;   // the middle ranks when nothing is missing (R is even)
     uint32_t colpar = 0;                          // parity of the column count: which umax slot is in use
 
     float v[ROWS][4];
@@ -814,22 +823,25 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
             __syncthreads();
             umax = rfl(*umax_slot);
         }
-        bool signs = umax >= 0x80000000u;
+        // special: some value carries a sign bit or is a NaN.  The raw bits are then no
+        // keys to select by, and a NaN is a missing sample that the ranks must not count.
+        bool special = umax > 0x7F800000u;
+        uint32_t k0 = k0_all, k1 = k1_all;
 
-        uint32_t s0, s1;
-        float med;
+        uint32_t s0 = 0, s1 = 0;
+        float med = 0.0f;
         bool have_mad = false;
-        if (!signs) {
+        if (!special) {
             uint32_t hlo = 0, hhi = 0;
             int hshift = 0;
             const bool one_round = block_select<NT, ROWS, LOG_NB, true>(
-                sh, XKeys<ROWS, true>{v}, __float_as_uint(v[0][0]), svalid, nsample, k0, k1, &s0, &s1,
-                &hlo, &hhi, &hshift, hinted, hint_lo, hint_hi, fused_umax ? umax_slot : nullptr, &umax);
-            signs = umax >= 0x80000000u;       // (only the fused pass can find this out here)
-        if (!signs) {
+                sh, XKeys<ROWS, true>{v}, __float_as_uint(v[0][0]), svalid, nsample, k0_all, k1_all, &s0,
+                &s1, &hlo, &hhi, &hshift, hinted, hint_lo, hint_hi, fused_umax ? umax_slot : nullptr, &umax);
+            special = umax > 0x7F800000u;      // (only the fused pass can find this out here)
+        if (!special) {
             med = 0.5f * (__uint_as_float(s0) + __uint_as_float(s1));
             if (one_round)
-                have_mad = mad_from_histogram<NT, ROWS, LOG_NB>(sh, v, med, hlo, hhi, hshift, k0, k1,
+                have_mad = mad_from_histogram<NT, ROWS, LOG_NB>(sh, v, med, hlo, hhi, hshift, k0_all, k1_all,
                                                                 hinted ? sh.hmad[m] : 0.0f, &s0, &s1);
             if (tid == 0) {
                 if (have_mad) {                 // keep the reach, follow the median
@@ -849,17 +861,45 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
         // the other slot is free again: every thread read it a column ago
         if (tid == 0) sh.umax[colpar ^ 1u] = 0;
         colpar ^= 1u;
-        if (signs) {
+        uint32_t present = R;
+        if (special) {
             if (tid == 0) sh.hok[m] = 0;
-            block_select<NT, ROWS, LOG_NB, false>(sh, XKeys<ROWS, false>{v}, key_of(v[0][0] + 0.0f),
-                                                  svalid, nsample, k0, k1, &s0, &s1);
-            med = 0.5f * (float_of_key(s0) + float_of_key(s1));
+            __syncthreads();    // (a counting pass given up above has just reset sh.below)
+            // samples present (padding lanes hold NaNs too): median and MAD are taken
+            // over them alone, the middle one(s) of `present`
+            // (tested on the bit patterns, against an opaque constant: the score loop's own
+            // tests of the same registers must not be merged with these and kept for later)
+            uint32_t np = 0;
+            const uint32_t absm = opaque_s(0x7FFFFFFFu);
+#pragma unroll
+            for (int j = 0; j < ROWS; ++j) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) np += (__float_as_uint(v[j][i]) & absm) <= 0x7F800000u ? 1u : 0u;
+                asm volatile("" : "+v"(np));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            np = wave_incl_scan(np);
+            if (lane == WAVE - 1 && np) atomicAdd(&sh.below, np);
+            __syncthreads();
+            present = rfl(sh.below);
+            __syncthreads();                    // everyone has read the count
+            if (tid == 0) sh.below = 0;
+            k0 = present ? (present - 1) / 2 : 0u;
+            k1 = present / 2;
+            if (present) {
+                const bool sv = svalid && v[0][0] == v[0][0];
+                block_select<NT, ROWS, LOG_NB, false>(sh, XKeys<ROWS, false>{v}, key_of(v[0][0] + 0.0f),
+                                                      sv, nsample, k0, k1, &s0, &s1);
+                // (an odd count has one middle value: no sum that could overflow)
+                med = k0 == k1 ? float_of_key(s0) : 0.5f * (float_of_key(s0) + float_of_key(s1));
+            }
         }
-        if (!have_mad)
+        if (!have_mad && present)
             block_select<NT, ROWS, LOG_NB, false>(sh, DKeys<ROWS>{v, med},
-                                                  __float_as_uint(fabsf(v[0][0] - med)), svalid, nsample,
-                                                  k0, k1, &s0, &s1);
-        const float mad = 0.5f * (__uint_as_float(s0) + __uint_as_float(s1));
+                                                  __float_as_uint(fabsf(v[0][0] - med)),
+                                                  svalid && v[0][0] == v[0][0], nsample, k0, k1, &s0, &s1);
+        float mad = k0 == k1 ? __uint_as_float(s0) : 0.5f * (__uint_as_float(s0) + __uint_as_float(s1));
+        if (!present) med = mad = __uint_as_float(0x7FC00000u);      // nothing to take a median of
         if (tid == 0) {
             a.med[t * M + m] = med;
             a.mad[t * M + m] = mad;
@@ -876,7 +916,7 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
         // The reciprocal route is exact while no intermediate can leave the normal
         // range: all x in [0, 2^59], 2^-34 <= med, 2^-60 <= s <= 2^60 (then every
         // non-zero |x - med| lies in [2^-59, 2^59]).
-        const bool fast = !signs && a.node_agg == 0 && umax <= 0x5D000000u && med >= 0x1p-34f &&
+        const bool fast = !special && a.node_agg == 0 && umax <= 0x5D000000u && med >= 0x1p-34f &&
                           s >= 0x1p-60f && s <= 0x1p60f;
         if (a.z) {   // optional full z output, recomputed so that the loops below stay lean
                      // (it must come first: they refill the registers with the next column)
@@ -887,6 +927,13 @@ __global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
                     float4 q;
                     q.x = ((v[j][0] + 0.0f) - med) / s; q.y = ((v[j][1] + 0.0f) - med) / s;
                     q.z = ((v[j][2] + 0.0f) - med) / s; q.w = ((v[j][3] + 0.0f) - med) / s;
+                    if (special) {              // a missing sample (NaN) scores 0
+                        const uint32_t absm = opaque_s(0x7FFFFFFFu);
+                        q.x = (__float_as_uint(v[j][0]) & absm) <= 0x7F800000u ? q.x : 0.0f;
+                        q.y = (__float_as_uint(v[j][1]) & absm) <= 0x7F800000u ? q.y : 0.0f;
+                        q.z = (__float_as_uint(v[j][2]) & absm) <= 0x7F800000u ? q.z : 0.0f;
+                        q.w = (__float_as_uint(v[j][3]) & absm) <= 0x7F800000u ? q.w : 0.0f;
+                    }
                     *reinterpret_cast<float4*>(zcol + rbase(j, tz)) = q;
                 }
             }

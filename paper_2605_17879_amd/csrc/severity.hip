@@ -8,6 +8,7 @@
 // primary-metric samples of the last min(T, W) steps by that step's cross-rank
 // median, sorts the at most 8192 quotients in LDS (bitonic network on
 // order-preserving integer keys) and takes the median of them minus one.
+// Missing samples (NaN) are left out.
 #include "gd_internal.h"
 
 namespace {
@@ -25,6 +26,7 @@ __device__ __forceinline__ float float_of_key(uint32_t k) {
 
 __global__ __launch_bounds__(SEV_NT) void severity_kernel(const gd_severity_args a) {
     __shared__ uint32_t q[SEV_MAX];
+    __shared__ uint32_t n_present;
     const uint32_t n = blockIdx.x, tid = threadIdx.x;
     const uint16_t* rc = reinterpret_cast<const uint16_t*>(a.state + a.lay.rank_count);
     const uint16_t* nc = reinterpret_cast<const uint16_t*>(a.state + a.lay.node_count);
@@ -36,6 +38,8 @@ __global__ __launch_bounds__(SEV_NT) void severity_kernel(const gd_severity_args
         return;
     }
     const uint32_t cnt = ws * 8;
+    if (tid == 0) n_present = 0;
+    __syncthreads();
     uint32_t P = 64;
     while (P < cnt) P <<= 1;                   // power of two >= cnt, <= SEV_MAX
     for (uint32_t i = tid; i < P; i += SEV_NT) {
@@ -48,7 +52,12 @@ __global__ __launch_bounds__(SEV_NT) void severity_kernel(const gd_severity_args
             if (a.dir > 0) r = xv / m;
             else if (a.dir < 0) r = m / xv;
             else r = xv >= m ? xv / m : m / xv;
-            k = key_of(r);
+            // a missing sample (NaN), or a step without a median, is left out: its key
+            // sorts with the padding
+            if (xv == xv && m == m) {
+                k = key_of(r);
+                atomicAdd(&n_present, 1u);
+            }
         }
         q[i] = k;
     }
@@ -66,8 +75,15 @@ __global__ __launch_bounds__(SEV_NT) void severity_kernel(const gd_severity_args
         }
     }
     if (tid == 0) {
-        // cnt is even: the two middle quotients added, then halved
-        const float mid = 0.5f * (float_of_key(q[cnt / 2 - 1]) + float_of_key(q[cnt / 2]));
+        const uint32_t np = n_present;
+        if (np == 0) {              // flagged, but nothing arrived inside the window
+            a.slowdown[n] = 0.0f;
+            a.tier[n] = 1;
+            return;
+        }
+        // the middle quotient, or the two middle ones added, then halved
+        const float mid = (np & 1) ? float_of_key(q[np / 2])
+                                   : 0.5f * (float_of_key(q[np / 2 - 1]) + float_of_key(q[np / 2]));
         const float s = mid - 1.0f;
         a.slowdown[n] = s;
         a.tier[n] = s >= a.severe ? 3 : (s >= a.moderate ? 2 : 1);

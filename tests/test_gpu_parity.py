@@ -333,3 +333,87 @@ def test_configuration_2_at_full_size():
     w = workload(2)
     say("case full-size", w.name)
     _full_size_case(w, seed=2, chunk=1000, min_flagged_nodes=30)  # 64 grey nodes, 3-20% slow
+
+
+NAN = float("nan")
+
+
+@pytest.mark.parametrize("R,M", [(64, 1), (72, 2), (1024, 4), (5000, 2), (16384, 3), (65536, 2)])
+def test_missing_samples(R, M, route):
+    """NaN = a sample that did not arrive: left out of median and MAD, z = 0, never
+    exceeds, adds nothing to its node.  Scattered ranks, whole nodes, a whole
+    column, odd and even numbers present, NaNs of either sign, next to columns with
+    nothing missing."""
+    T = 6
+    say(f"case missing samples R={R} M={M}")
+    g = torch.Generator().manual_seed(R + 7 * M)
+    x = torch.exp(0.02 * torch.randn((T, M, R), generator=g, dtype=torch.float64)).to(torch.float32)
+    x[:, :, 16:24] *= 1.2                                  # a slow node
+    N = R // 8
+    x[0, 0, torch.randperm(R, generator=g)[: max(1, R // 50)]] = NAN     # scattered, even or odd count
+    x[1, 0, 5] = NAN                                       # a single one: an odd number present
+    x[1, 0, 16:19] = NAN                                   # part of the slow node
+    x[2, M - 1, 8 * (N // 2): 8 * (N // 2) + 8] = NAN      # a silent node
+    x[3, 0, :] = NAN                                       # nothing arrived for this metric
+    x[4, 0, : R - 3] = NAN                                 # three samples left
+    x[5, 0, 1::2] = -x[5, 0, 1::2]                         # signs, and NaNs with the sign bit set
+    neg_nan = torch.tensor([0xFFC00001], dtype=torch.int64).to(torch.int32).view(torch.float32)
+    x[5, 0, 7] = neg_nan[0]
+    x[5, 0, 32 % R] = NAN
+    dirs = tuple((1, -1, 0, 1)[m % 4] for m in range(M))
+    for thr, agg in ((3.5, oracle.NODE_SUM_SCALED), (-0.5, oracle.NODE_MAX)):
+        p = oracle_params(R=R, M=M, W=4, k=2, thr=thr, node_agg=agg, directions=dirs, min_signals=1)
+        rep = run_and_compare(p, x, topk_k=min(8, N), chunks=[2, 4], label=f"missing-R{R}-thr{thr}")
+        say("  report", rep)
+        assert rep["z_bit_exact"]
+
+
+def test_severity_with_missing_samples():
+    R, M, W, T = 1024, 2, 8, 20
+    say("case severity with missing samples")
+    g = torch.Generator().manual_seed(77)
+    x = torch.exp(0.02 * torch.randn((T, M, R), generator=g, dtype=torch.float64)).to(torch.float32)
+    for i, s in enumerate((1.08, 1.15, 1.3, 1.12)):
+        x[:, :, (3 + 7 * i) * 8:(3 + 7 * i) * 8 + 8] *= s
+    x[T - 5:, 0, 3 * 8: 3 * 8 + 5] = NAN            # part of a slow node, part of the window
+    x[T - 8:, 0, 10 * 8 + 1] = NAN                   # one GPU of a slow node, the whole window: 56 left
+    x[T - 3, 0, 17 * 8: 17 * 8 + 8] = NAN            # one step of a slow node
+    x[T - 6:, 0, 24 * 8: 24 * 8 + 8] = NAN           # a slow node that fell silent: 2 steps x 8 left
+    x[T - 2, 0, ::3] = NAN                           # a step with many samples missing
+    p = oracle_params(R=R, M=M, W=W, k=3, directions=(1, 1), min_signals=1)
+    d = oracle.detect(p, x.numpy(), topk_k=1)
+    det = detector_for(p)
+    out = gpu_score(det, x, want_z=False)
+    compare_scores(d["scores"], out, "scores")
+    det.update_window(out, T)
+    rep = compare_severity(p, d, det, x, out, label="missing")
+    say("  nodes per tier", rep)
+    assert sum(rep["tiers"][1:]) >= 3
+    det.close()
+
+
+def test_missing_samples_and_signs_arriving_in_the_middle_of_a_run():
+    """Two steps per workgroup and more (65 536 ranks, 600 steps): the second step of a
+    run starts from the first one's median as a hint and finds the column's largest
+    bit pattern during its counting pass -- which then has to notice NaNs and signs."""
+    R, M, T = 65536, 2, 600
+    say("case missing samples inside hinted runs")
+    g = torch.Generator().manual_seed(5)
+    x = torch.exp(0.02 * torch.randn((T, M, R), generator=g, dtype=torch.float64)).to(torch.float32)
+    x[:, :, 4096:4104] *= 1.1
+    for t in range(1, T, 7):                       # odd steps are the second of their run
+        x[t, 0, (t * 37) % R] = NAN                # a single missing sample
+    for t in range(3, T, 31):
+        x[t, 1, torch.randperm(R, generator=g)[:5000]] = NAN
+    x[301, 0, ::2] = NAN                           # half of the column
+    x[303, 1, :] = NAN                             # all of it
+    x[305, 0, 100] = -x[305, 0, 100]               # a sign
+    x[401, 1, 7] = -0.0
+    p = oracle_params(R=R, M=M, W=16, k=8, directions=(1, -1), min_signals=1)
+    det = detector_for(p)
+    det.set_streaming_steps(0)
+    out = gpu_score(det, x, want_z=False)
+    o = oracle.score(p, x.numpy(), want_z=False)
+    rep = compare_scores(o, out, "hinted runs with missing samples")
+    say("  report", rep)
+    det.close()

@@ -178,3 +178,23 @@ def test_negative_zero_reads_as_zero_and_empty_history():
     assert np.isinf(slow[0]) and slow[0] > 0          # 1 / +0, not 1 / -0
     slow, tier = oracle.severity(p, x[:0], med[:0], flag)
     assert not slow.any() and not tier.any()
+
+
+def test_missing_samples_are_left_out_of_the_quotients():
+    p = params(W=4)
+    T = 4
+    x = flat_history(T, p.M, p.R, 1.0)
+    med = np.ones((T, p.M), np.float32)
+    nan = np.float32("nan")
+    x[:, 0, 8:16] = 1.5
+    x[1:, 0, 8:13] = nan            # node 1: 8 + 3*3 = 17 quotients left (odd), all 1.5
+    x[:, 0, 16:24] = [1.0, 1.1, 1.2, 1.3, 1.4, nan, nan, nan]     # node 2: 5 per step, 20 in all
+    x[:, 0, 24:32] = nan            # node 3: nothing arrived
+    med[0, 0] = nan                 # and a step without a median counts for nobody
+    flag = np.ones(p.N, np.uint8)
+    slow, tier = oracle.severity(p, x, med, flag)
+    assert slow[1] == np.float32(0.5) and tier[1] == 3
+    q = np.sort(np.tile(np.array([1.0, 1.1, 1.2, 1.3, 1.4], np.float32), 3))     # 3 steps count
+    assert slow[2] == np.float32(np.median(q)) - np.float32(1.0)
+    assert slow[3] == 0.0 and tier[3] == 1
+    assert slow[0] == 0.0 and tier[0] == 1
