@@ -66,9 +66,18 @@ def cpu_baseline(w, x_dev, sample_steps: int) -> dict:
     t0 = time.perf_counter()
     oracle.detect(p, xs, topk_k=w.topk, want_z=False)
     dt = time.perf_counter() - t0
-    return {"value": xs.size / dt, "unit": "samples/s", "cores": oracle.num_threads(),
-            "kind": "oracle",
-            "sample": f"first {sample_steps} of {w.T} steps ({xs.size} samples, {dt:.2f} s wall)"}
+    cores = oracle.num_threads()
+    # one core, on a sample sized to take a few seconds
+    one_steps = max(1, min(sample_steps, sample_steps * 4 // max(cores, 1) // 4))
+    oracle.set_threads(1)
+    t1 = time.perf_counter()
+    oracle.detect(p, xs[:one_steps], topk_k=w.topk, want_z=False)
+    dt1 = time.perf_counter() - t1
+    oracle.set_threads(cores)
+    return {"value": xs.size / dt, "unit": "samples/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {sample_steps} of {w.T} steps ({xs.size} samples, {dt:.2f} s wall)",
+            "single_thread": {"value": xs[:one_steps].size / dt1, "unit": "samples/s",
+                              "sample": f"first {one_steps} steps, {dt1:.2f} s wall"}}
 
 
 def streaming_latency(torch, n_steps: int) -> dict:
@@ -155,6 +164,16 @@ def main() -> int:
             torch.add(src, 1.0, out=dst)            # one elementwise kernel: read src, write dst
         torch.cuda.synchronize()
         del dst
+    # the ceiling of a single pass: the scoring kernel's loads alone over the same tensor
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    pe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
+    with torch.cuda.stream(stream):
+        for s0, s1 in pe:
+            s0.record(stream)
+            det.probe_read(x, sink, stream)
+            s1.record(stream)
+        torch.cuda.synchronize()
+    read_ms = sorted(s0.elapsed_time(s1) for s0, s1 in pe)[2]
     ms_per_step = 1e3 * dt / a.steps
     score_ms = sum(s.elapsed_time(e) for s, e in ev) / a.steps
     alg = algorithmic_bytes_per_launch(w.R, w.M, w.T)
@@ -170,7 +189,9 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": "score_kernel<1024,16,12,true>", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(), "algorithmic_bytes": alg,
-                     "avg_launch_ms": score_ms},
+                     "avg_launch_ms": score_ms,
+                     "read_only_ceiling": {"GB/s": x.numel() * 4 / (read_ms * 1e-3) / 1e9, "ms": read_ms,
+                                           "what": "the same loads with no arithmetic (gd_probe_read)"}},
     }
     if not a.no_cpu:
         res["cpu_baseline"] = cpu_baseline(w, x, a.cpu_sample_steps)

@@ -207,6 +207,16 @@ gd_status gd_topk_nodes(gd_handle h, uint32_t k, int32_t* d_idx, uint64_t* d_key
 gd_status gd_severity(gd_handle h, const float* d_x, uint32_t T, const float* d_med, float moderate,
                       float severe, float* d_node_slowdown, uint8_t* d_node_tier, void* stream);
 
+/*
+ * Diagnostic for benchmarks: reads the first n_bytes (rounded down to a multiple of
+ * 256 KiB) of d_x with the scoring kernel's own load pattern and does nothing else,
+ * so that its duration next to gd_score_batch's gives the ceiling of a single pass
+ * over the data on this chip.  d_x 16-byte aligned device memory; d_sink one u32 of
+ * device memory that the call may write.
+ */
+gd_status gd_probe_read(gd_handle h, const float* d_x, uint64_t n_bytes, uint32_t* d_sink,
+                        void* stream);
+
 /* Text of the last error on this handle (or of the last failed gd_create when
  * h is NULL).  The pointer stays valid until the next call on the handle. */
 const char* gd_last_error(gd_handle h);

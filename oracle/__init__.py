@@ -63,6 +63,8 @@ def _load():
         _lib.go_score.restype = None
         _lib.go_num_threads.argtypes = []
         _lib.go_num_threads.restype = ctypes.c_int
+        _lib.go_set_threads.argtypes = [ctypes.c_int]
+        _lib.go_set_threads.restype = None
         _lib.go_median.argtypes = [vp, ctypes.c_uint64]
         _lib.go_median.restype = ctypes.c_float
         _lib.go_window.argtypes = [ctypes.c_uint32, vp, ctypes.c_uint64, ctypes.c_uint32,
@@ -145,6 +147,11 @@ def _ptr(a: Optional[np.ndarray]):
 def num_threads() -> int:
     """Threads the oracle's column-parallel loops use."""
     return int(_load().go_num_threads())
+
+
+def set_threads(n: int) -> None:
+    """Threads for the column-parallel loops from now on (timing one core: n = 1)."""
+    _load().go_set_threads(int(n))
 
 
 def median(v: np.ndarray) -> np.float32:

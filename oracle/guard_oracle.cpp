@@ -100,6 +100,15 @@ int go_num_threads(void) {
 #endif
 }
 
+// Limit the column-parallel loops to n threads (n >= 1), e.g. to time one core.
+void go_set_threads(int n) {
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 // The median rule on its own (any count >= 1), after reading -0 as +0.
 float go_median(const float* v, uint64_t n) {
     std::vector<float> w(n);

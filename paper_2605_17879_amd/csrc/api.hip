@@ -253,6 +253,17 @@ gd_status gd_severity(gd_handle h, const float* d_x, uint32_t T, const float* d_
     return GD_OK;
 }
 
+gd_status gd_probe_read(gd_handle h, const float* d_x, uint64_t n_bytes, uint32_t* d_sink,
+                        void* stream) {
+    if (!h) return GD_ERR_INVALID_ARG;
+    if (!d_x || !d_sink) return fail(h, GD_ERR_INVALID_ARG, "gd_probe_read: null pointer");
+    if (((uintptr_t)d_x & 15) || ((uintptr_t)d_sink & 3))
+        return fail(h, GD_ERR_INVALID_ARG, "gd_probe_read: misaligned pointer");
+    hipError_t e = gd_launch_read_probe(d_x, n_bytes, d_sink, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(h, e, "gd_probe_read");
+    return GD_OK;
+}
+
 const char* gd_last_error(gd_handle h) { return h ? h->err.c_str() : g_create_error.c_str(); }
 
 }  // extern "C"

@@ -84,6 +84,7 @@ struct gd_severity_args {
 
 hipError_t gd_launch_score(const gd_score_args& a, hipStream_t s);
 hipError_t gd_launch_severity(const gd_severity_args& a, hipStream_t s);
+hipError_t gd_launch_read_probe(const float* d_x, uint64_t n_bytes, uint32_t* d_sink, hipStream_t s);
 hipError_t gd_launch_window(const gd_window_args& a, hipStream_t s);
 hipError_t gd_launch_flags(const gd_flags_args& a, hipStream_t s);
 hipError_t gd_launch_topk(const gd_topk_args& a, hipStream_t s);

@@ -1121,6 +1121,28 @@ __global__ __launch_bounds__(256) void combine_kernel(const gd_score_args a) {
     }
 }
 
+// Diagnostic: the scoring kernel's loads and nothing else -- persistent 1024-thread
+// workgroups, each reading a contiguous run of 256 KB blocks, sixteen float4 loads
+// per thread and block -- as the ceiling that a single pass over the data has.
+__global__ __launch_bounds__(1024) void read_probe_kernel(const float* x, uint64_t n_blocks,
+                                                          uint32_t* sink) {
+    constexpr uint32_t BLOCK_FLOATS = 1024 * 4 * 16;
+    const uint64_t per = (n_blocks + gridDim.x - 1) / gridDim.x;
+    const uint64_t b0 = blockIdx.x * per, b1 = b0 + per < n_blocks ? b0 + per : n_blocks;
+    uint32_t acc = 0;
+    for (uint64_t b = b0; b < b1; ++b) {
+        const float* p = x + b * BLOCK_FLOATS + threadIdx.x * 4;
+        float4 q[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) q[j] = *reinterpret_cast<const float4*>(p + j * 4096);
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            acc = max(acc, max(max(__float_as_uint(q[j].x), __float_as_uint(q[j].y)),
+                               max(__float_as_uint(q[j].z), __float_as_uint(q[j].w))));
+    }
+    if (acc == 0xFFFFFFFFu) *sink = acc;      // (keeps the loads alive; NaN patterns aside, never true)
+}
+
 int compute_units(hipError_t* err) {
     static int n_cu = 0;
     *err = hipSuccess;
@@ -1187,6 +1209,17 @@ hipError_t launch(const gd_score_args& a, hipStream_t s) {
 }
 
 }  // namespace
+
+hipError_t gd_launch_read_probe(const float* d_x, uint64_t n_bytes, uint32_t* d_sink, hipStream_t s) {
+    const uint64_t n_blocks = n_bytes / (256 * 1024);
+    if (n_blocks == 0) return hipSuccess;
+    hipError_t e;
+    const int n_cu = compute_units(&e);
+    if (e != hipSuccess) return e;
+    const uint32_t grid = (uint32_t)(n_blocks < (uint64_t)n_cu ? n_blocks : (uint64_t)n_cu);
+    hipLaunchKernelGGL(read_probe_kernel, dim3(grid), dim3(1024), 0, s, d_x, n_blocks, d_sink);
+    return hipGetLastError();
+}
 
 // Pick the register tiling for R: NT threads x ROWS float4 rows hold NT*4*ROWS ranks.
 hipError_t gd_launch_score(const gd_score_args& a, hipStream_t s) {

@@ -23,7 +23,7 @@ NODE_MAX = 1
 
 EXPORTS = ("gd_default_config", "gd_create", "gd_destroy", "gd_state_bytes", "gd_bind_state",
            "gd_set_streaming_steps", "gd_score_batch", "gd_update_window", "gd_flags",
-           "gd_topk_nodes", "gd_severity", "gd_last_error")
+           "gd_topk_nodes", "gd_severity", "gd_probe_read", "gd_last_error")
 
 
 class GuardError(RuntimeError):
@@ -80,6 +80,8 @@ def load_library() -> ctypes.CDLL:
     lib.gd_topk_nodes.restype = ctypes.c_int
     lib.gd_severity.argtypes = [vp, vp, u32, vp, ctypes.c_float, ctypes.c_float, vp, vp, vp]
     lib.gd_severity.restype = ctypes.c_int
+    lib.gd_probe_read.argtypes = [vp, vp, u64, vp, vp]
+    lib.gd_probe_read.restype = ctypes.c_int
     lib.gd_last_error.argtypes = [vp]
     lib.gd_last_error.restype = ctypes.c_char_p
     _lib = lib
@@ -234,6 +236,11 @@ class Detector:
         assert x.is_cuda and x.is_contiguous() and tuple(x.shape) == (T, self.M, self.R)
         self._check(self.lib.gd_severity(self.h, x.data_ptr(), T, _p(out["med"]), moderate, severe,
                                          _p(sev["slowdown"]), _p(sev["tier"]), self._stream(stream)))
+
+    def probe_read(self, x, sink, stream=None):
+        """Stream x through the chip with the scoring kernel's load pattern (a diagnostic)."""
+        self._check(self.lib.gd_probe_read(self.h, x.data_ptr(), x.numel() * x.element_size(),
+                                           sink.data_ptr(), self._stream(stream)))
 
     def alloc_topk(self, k: int) -> dict:
         torch, d = self._torch, self.device
