@@ -186,7 +186,7 @@ def main() -> int:
         "config": {"workload": f"{w.R} ranks x {w.T} steps x {w.M} metrics fp32 "
                                f"(heavy-tailed noise, W={w.W}, k={w.k}, top-{w.topk}); "
                                "score_batch + update_window + flags + topk_nodes per step"},
-        "roofline": {"bound": "hbm", "kernel": "score_kernel<1024,16,12,true>", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "score_kernel<1024,16,12,true,false>", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(), "algorithmic_bytes": alg,
                      "avg_launch_ms": score_ms,
