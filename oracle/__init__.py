@@ -13,8 +13,9 @@ stragglers injected with a constructed margin, spike immunity, brute-force
 top-k; for the severity tiers: exact rational arithmetic on small cases,
 ``numpy.median`` of the quotients, constructed slowdowns, the window's extent,
 both directions, tier boundaries; for missing samples (NaN): ``numpy.nanmedian``,
-exact rational arithmetic, and the same cluster without its silent nodes.  No
-function here is "parity unpinned".
+exact rational arithmetic, and the same cluster without its silent nodes; for
+the single-node sweep: exact rational arithmetic, numpy medians, constructed
+throttling and asymmetry.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -74,6 +75,9 @@ def _load():
         _lib.go_node_flag_byte.restype = None
         _lib.go_topk.argtypes = [ctypes.c_uint32, vp, vp, ctypes.c_uint32, vp, vp]
         _lib.go_topk.restype = None
+        _lib.go_sweep.argtypes = [ctypes.c_uint32, vp, vp, ctypes.c_float, ctypes.c_float,
+                                  ctypes.c_float, vp, vp, vp, vp]
+        _lib.go_sweep.restype = None
         _lib.go_severity.argtypes = [ctypes.POINTER(_Cfg), vp, ctypes.c_uint64, vp, vp,
                                      ctypes.c_float, ctypes.c_float, vp, vp]
         _lib.go_severity.restype = None
@@ -242,6 +246,23 @@ def severity(p: Params, x: np.ndarray, med: np.ndarray, node_flag_byte: np.ndarr
     _load().go_severity(ctypes.byref(c), _ptr(x), T, _ptr(med), _ptr(nfb), moderate, severe,
                         _ptr(slow), _ptr(tier))
     return slow, tier
+
+
+def sweep(flops: np.ndarray, bw: np.ndarray, tol_compute: float = 0.05, tol_sym: float = 0.10,
+          tol_bw: float = 0.15):
+    """Single-node sweep scoring of B nodes: flops[B][8], bw[B][8][8] ->
+    (shortfall[B][8] f32, gpu_mask[B] u8, link_mask[B] u32, verdict[B] u8)."""
+    flops = np.ascontiguousarray(flops, np.float32)
+    bw = np.ascontiguousarray(bw, np.float32)
+    B = flops.shape[0]
+    assert flops.shape == (B, 8) and bw.shape == (B, 8, 8)
+    sf = np.empty((B, 8), np.float32)
+    gm = np.empty(B, np.uint8)
+    lm = np.empty(B, np.uint32)
+    vd = np.empty(B, np.uint8)
+    _load().go_sweep(B, _ptr(flops), _ptr(bw), tol_compute, tol_sym, tol_bw, _ptr(sf), _ptr(gm),
+                     _ptr(lm), _ptr(vd))
+    return sf, gm, lm, vd
 
 
 def detect(p: Params, x: np.ndarray, topk_k: int, want_z: bool = False):

@@ -334,4 +334,55 @@ void go_severity(const go_config* c, const float* x, uint64_t T, const float* me
     }
 }
 
+// Single-node sweep scoring (Section 5, "Single-Node Sweep": consistent sustained
+// throughput across the GPUs of a node; connectivity and symmetry of the pairwise
+// intra-node bandwidth).  Reading, per node b of n_nodes, G = 8:
+//   flops[b][g]      sustained throughput of GPU g
+//   bw[b][i][j]      bandwidth measured from GPU i to GPU j (the diagonal is ignored)
+//   m8   = median of the 8 throughputs (rule "median");
+//   shortfall[b][g] = (m8 - flops_g) / m8;          gpu_mask bit g : shortfall > tol_compute
+//   m56  = median of the 56 off-diagonal bandwidths;
+//   for every pair i < j, numbered p = 0..27 row by row ((0,1), (0,2), ... (6,7)):
+//     hi = max(bw_ij, bw_ji), lo = min(bw_ij, bw_ji)
+//     link_mask bit p : (hi - lo) / hi > tol_sym  ||  (m56 - lo) / m56 > tol_bw
+//   verdict[b] = (gpu_mask != 0) | (link_mask != 0) << 1
+// every operation rounded to fp32.
+void go_sweep(uint32_t n_nodes, const float* flops, const float* bw, float tol_compute, float tol_sym,
+              float tol_bw, float* shortfall, uint8_t* gpu_mask, uint32_t* link_mask,
+              uint8_t* verdict) {
+    for (uint32_t b = 0; b < n_nodes; ++b) {
+        const float* f = flops + (size_t)b * 8;
+        const float* w = bw + (size_t)b * 64;
+        std::vector<float> v(f, f + 8);
+        const float m8 = median_by_sort(v);
+        uint8_t gm = 0;
+        for (int g = 0; g < 8; ++g) {
+            const float d = m8 - f[g];
+            const float sf = d / m8;
+            shortfall[(size_t)b * 8 + g] = sf;
+            if (sf > tol_compute) gm |= (uint8_t)(1u << g);
+        }
+        std::vector<float> off;
+        for (int i = 0; i < 8; ++i)
+            for (int j = 0; j < 8; ++j)
+                if (i != j) off.push_back(w[i * 8 + j]);
+        const float m56 = median_by_sort(off);
+        uint32_t lm = 0;
+        int p = 0;
+        for (int i = 0; i < 8; ++i)
+            for (int j = i + 1; j < 8; ++j, ++p) {
+                const float a = w[i * 8 + j], c = w[j * 8 + i];
+                const float hi = std::max(a, c), lo = std::min(a, c);
+                const float gap = hi - lo;
+                const float asym = gap / hi;
+                const float d = m56 - lo;
+                const float sf = d / m56;
+                if (asym > tol_sym || sf > tol_bw) lm |= 1u << p;
+            }
+        gpu_mask[b] = gm;
+        link_mask[b] = lm;
+        verdict[b] = (uint8_t)((gm ? 1 : 0) | (lm ? 2 : 0));
+    }
+}
+
 }  // extern "C"
