@@ -208,6 +208,29 @@ gd_status gd_severity(gd_handle h, const float* d_x, uint32_t T, const float* d_
                       float severe, float* d_node_slowdown, uint8_t* d_node_tier, void* stream);
 
 /*
+ * Scoring of single-node sweep results (Section 5, "Single-Node Sweep": sustained
+ * throughput consistent across the GPUs of a node; pairwise intra-node bandwidth
+ * connected and symmetric), for n_nodes nodes of 8 GPUs at once.  Independent of
+ * the handle's configuration and state.
+ *   d_flops [n_nodes][8]    f32 in   sustained throughput of each GPU
+ *   d_bw    [n_nodes][8][8] f32 in   bandwidth from GPU i to GPU j; the diagonal is ignored
+ *   d_gpu_shortfall [n_nodes][8] f32 out  (m8 - flops_g) / m8, m8 = median of the node's 8
+ *                                         throughputs (the two middle ones added, then halved)
+ *   d_gpu_mask  [n_nodes] u8  out  bit g: shortfall_g > tol_compute
+ *   d_link_mask [n_nodes] u32 out  bit p for the pair i < j numbered row by row ((0,1), (0,2),
+ *                                  ..., (6,7) = 27): with hi / lo the larger / smaller of
+ *                                  bw[i][j] and bw[j][i] and m56 the median of the 56
+ *                                  off-diagonal entries, (hi - lo) / hi > tol_sym or
+ *                                  (m56 - lo) / m56 > tol_bw
+ *   d_verdict   [n_nodes] u8  out  bit 0: some GPU bit set; bit 1: some link bit set
+ * Every operation is rounded to fp32.  Non-finite or non-positive inputs give
+ * unspecified results for that node (no fault).  n_nodes == 0 is a no-op.
+ */
+gd_status gd_sweep_score(gd_handle h, const float* d_flops, const float* d_bw, uint32_t n_nodes,
+                         float tol_compute, float tol_sym, float tol_bw, float* d_gpu_shortfall,
+                         uint8_t* d_gpu_mask, uint32_t* d_link_mask, uint8_t* d_verdict, void* stream);
+
+/*
  * Diagnostic for benchmarks: reads the first n_bytes (rounded down to a multiple of
  * 256 KiB) of d_x with the scoring kernel's own load pattern and does nothing else,
  * so that its duration next to gd_score_batch's gives the ceiling of a single pass

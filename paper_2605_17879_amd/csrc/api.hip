@@ -253,6 +253,25 @@ gd_status gd_severity(gd_handle h, const float* d_x, uint32_t T, const float* d_
     return GD_OK;
 }
 
+gd_status gd_sweep_score(gd_handle h, const float* d_flops, const float* d_bw, uint32_t n_nodes,
+                         float tol_compute, float tol_sym, float tol_bw, float* d_gpu_shortfall,
+                         uint8_t* d_gpu_mask, uint32_t* d_link_mask, uint8_t* d_verdict, void* stream) {
+    if (!h) return GD_ERR_INVALID_ARG;
+    if (n_nodes == 0) return GD_OK;
+    if (!d_flops || !d_bw || !d_gpu_shortfall || !d_gpu_mask || !d_link_mask || !d_verdict)
+        return fail(h, GD_ERR_INVALID_ARG, "gd_sweep_score: null pointer");
+    if (((uintptr_t)d_flops & 3) || ((uintptr_t)d_bw & 3) || ((uintptr_t)d_gpu_shortfall & 3) ||
+        ((uintptr_t)d_link_mask & 3))
+        return fail(h, GD_ERR_INVALID_ARG, "gd_sweep_score: misaligned pointer");
+    gd_sweep_args a;
+    a.flops = d_flops; a.bw = d_bw; a.shortfall = d_gpu_shortfall; a.gpu_mask = d_gpu_mask;
+    a.link_mask = d_link_mask; a.verdict = d_verdict; a.n_nodes = n_nodes;
+    a.tol_compute = tol_compute; a.tol_sym = tol_sym; a.tol_bw = tol_bw;
+    hipError_t e = gd_launch_sweep(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(h, e, "gd_sweep_score");
+    return GD_OK;
+}
+
 gd_status gd_probe_read(gd_handle h, const float* d_x, uint64_t n_bytes, uint32_t* d_sink,
                         void* stream) {
     if (!h) return GD_ERR_INVALID_ARG;

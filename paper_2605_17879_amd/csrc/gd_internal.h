@@ -82,7 +82,19 @@ struct gd_severity_args {
     float moderate, severe;
 };
 
+struct gd_sweep_args {
+    const float* flops;   // [n_nodes][8]
+    const float* bw;      // [n_nodes][8][8]
+    float* shortfall;     // [n_nodes][8]
+    uint8_t* gpu_mask;    // [n_nodes]
+    uint32_t* link_mask;  // [n_nodes]
+    uint8_t* verdict;     // [n_nodes]
+    uint32_t n_nodes;
+    float tol_compute, tol_sym, tol_bw;
+};
+
 hipError_t gd_launch_score(const gd_score_args& a, hipStream_t s);
+hipError_t gd_launch_sweep(const gd_sweep_args& a, hipStream_t s);
 hipError_t gd_launch_severity(const gd_severity_args& a, hipStream_t s);
 hipError_t gd_launch_read_probe(const float* d_x, uint64_t n_bytes, uint32_t* d_sink, hipStream_t s);
 hipError_t gd_launch_window(const gd_window_args& a, hipStream_t s);

@@ -23,7 +23,7 @@ NODE_MAX = 1
 
 EXPORTS = ("gd_default_config", "gd_create", "gd_destroy", "gd_state_bytes", "gd_bind_state",
            "gd_set_streaming_steps", "gd_score_batch", "gd_update_window", "gd_flags",
-           "gd_topk_nodes", "gd_severity", "gd_probe_read", "gd_last_error")
+           "gd_topk_nodes", "gd_severity", "gd_sweep_score", "gd_probe_read", "gd_last_error")
 
 
 class GuardError(RuntimeError):
@@ -80,6 +80,9 @@ def load_library() -> ctypes.CDLL:
     lib.gd_topk_nodes.restype = ctypes.c_int
     lib.gd_severity.argtypes = [vp, vp, u32, vp, ctypes.c_float, ctypes.c_float, vp, vp, vp]
     lib.gd_severity.restype = ctypes.c_int
+    f32 = ctypes.c_float
+    lib.gd_sweep_score.argtypes = [vp, vp, vp, u32, f32, f32, f32, vp, vp, vp, vp, vp]
+    lib.gd_sweep_score.restype = ctypes.c_int
     lib.gd_probe_read.argtypes = [vp, vp, u64, vp, vp]
     lib.gd_probe_read.restype = ctypes.c_int
     lib.gd_last_error.argtypes = [vp]
@@ -236,6 +239,23 @@ class Detector:
         assert x.is_cuda and x.is_contiguous() and tuple(x.shape) == (T, self.M, self.R)
         self._check(self.lib.gd_severity(self.h, x.data_ptr(), T, _p(out["med"]), moderate, severe,
                                          _p(sev["slowdown"]), _p(sev["tier"]), self._stream(stream)))
+
+    def sweep_score(self, flops, bw, tol_compute: float = 0.05, tol_sym: float = 0.10,
+                    tol_bw: float = 0.15, stream=None) -> dict:
+        """Single-node sweep scoring of flops[B][8], bw[B][8][8] (device tensors)."""
+        torch, d = self._torch, self.device
+        B = flops.shape[0]
+        assert flops.is_cuda and flops.is_contiguous() and tuple(flops.shape) == (B, 8)
+        assert bw.is_cuda and bw.is_contiguous() and tuple(bw.shape) == (B, 8, 8)
+        out = dict(shortfall=torch.empty((B, 8), dtype=torch.float32, device=d),
+                   gpu_mask=torch.empty(B, dtype=torch.uint8, device=d),
+                   link_mask=torch.empty(B, dtype=torch.int32, device=d),
+                   verdict=torch.empty(B, dtype=torch.uint8, device=d))
+        self._check(self.lib.gd_sweep_score(self.h, flops.data_ptr(), bw.data_ptr(), B, tol_compute,
+                                            tol_sym, tol_bw, _p(out["shortfall"]), _p(out["gpu_mask"]),
+                                            _p(out["link_mask"]), _p(out["verdict"]),
+                                            self._stream(stream)))
+        return out
 
     def probe_read(self, x, sink, stream=None):
         """Stream x through the chip with the scoring kernel's load pattern (a diagnostic)."""

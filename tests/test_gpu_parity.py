@@ -417,3 +417,31 @@ def test_missing_samples_and_signs_arriving_in_the_middle_of_a_run():
     rep = compare_scores(o, out, "hinted runs with missing samples")
     say("  report", rep)
     det.close()
+
+
+@pytest.mark.parametrize("B", [1, 5, 4096, 8192 + 3])
+def test_single_node_sweep_scoring(B):
+    say(f"case sweep scoring B={B}")
+    rng = np.random.default_rng(B)
+    flops = (400.0 * np.exp(0.03 * rng.standard_normal((B, 8)))).astype(np.float32)
+    bw = (300.0 * np.exp(0.04 * rng.standard_normal((B, 8, 8)))).astype(np.float32)
+    for b in range(0, B, 3):                       # throttled GPUs, one-way and two-way slow links
+        flops[b, rng.integers(8)] *= np.float32(rng.uniform(0.6, 0.97))
+    for b in range(1, B, 4):
+        i, j = rng.choice(8, 2, replace=False)
+        bw[b, i, j] *= np.float32(rng.uniform(0.4, 0.95))
+        if b % 8 == 1:
+            bw[b, j, i] = bw[b, i, j]
+    bw[0, :, :] = bw[0, 0, 1]                      # ties everywhere
+    p = oracle_params(R=64, M=1, W=2, k=1)
+    det = detector_for(p)
+    for tc, ts, tb in ((0.05, 0.10, 0.15), (0.0, 0.0, 0.0), (0.5, 0.02, 0.9)):
+        want = oracle.sweep(flops, bw, tc, ts, tb)
+        got = det.sweep_score(torch.from_numpy(flops).cuda(), torch.from_numpy(bw).cuda(), tc, ts, tb)
+        torch.cuda.synchronize()
+        assert np.array_equal(got["shortfall"].cpu().numpy().view(np.uint32), want[0].view(np.uint32))
+        assert np.array_equal(got["gpu_mask"].cpu().numpy(), want[1])
+        assert np.array_equal(got["link_mask"].cpu().numpy().view(np.uint32), want[2])
+        assert np.array_equal(got["verdict"].cpu().numpy(), want[3])
+    say("  verdicts", np.bincount(want[3], minlength=4).tolist())
+    det.close()
