@@ -25,6 +25,11 @@ constexpr int WAVE = 64;
 constexpr int WIN_NT = 256;
 
 // Items [0, R) are ranks, then, starting at a fresh workgroup, items [0, N) are nodes.
+// RING > 0: the window is RING blocks of 64 steps long, so the bits leaving during a
+// block are the bits that entered RING blocks earlier -- already transposed then and
+// kept in registers; only the blocks that reach back beyond the batch transpose ring
+// words.  RING == 0: any window length, two transposes per block.
+template <int RING>
 __global__ __launch_bounds__(WIN_NT) void window_kernel(const gd_window_args a) {
     const uint32_t rank_blocks = (a.R + WIN_NT - 1) / WIN_NT;
     const bool is_node = blockIdx.x >= rank_blocks;
@@ -48,9 +53,11 @@ __global__ __launch_bounds__(WIN_NT) void window_kernel(const gd_window_args a) 
         if (s < T) {
             *win = anom[(size_t)s * words + word];
             const uint64_t t = a.first_step + s;
-            if (t >= W)
-                *wout = s >= W ? anom[(size_t)(s - W) * words + word]
-                               : ring[(size_t)(t % W) * words + word];
+            if (t >= W) {
+                if (s < W) *wout = ring[(size_t)(t % W) * words + word];
+                else if (RING == 0) *wout = anom[(size_t)(s - W) * words + word];
+                // (RING > 0: these bits are still in registers from RING blocks ago)
+            }
         }
     };
 
@@ -58,8 +65,9 @@ __global__ __launch_bounds__(WIN_NT) void window_kernel(const gd_window_args a) 
     int32_t f = live ? first[item] : 0;
     // Blocks are fetched AHEAD blocks in advance (the loop is latency-bound: one wave
     // per word column walks its steps in order).
-    constexpr int AHEAD = 4;
+    constexpr int AHEAD = RING > 4 ? RING : 4;
     uint64_t win[AHEAD], wout[AHEAD];
+    uint64_t entered[RING > 0 ? RING : 1];      // transposed entering bits of the last RING blocks
 #pragma unroll
     for (int q = 0; q < AHEAD; ++q) fetch(q * WAVE + lane, &win[q], &wout[q]);
     for (uint32_t s0 = 0; s0 < T; s0 += AHEAD * WAVE) {
@@ -71,7 +79,13 @@ __global__ __launch_bounds__(WIN_NT) void window_kernel(const gd_window_args a) 
             fetch(sq + AHEAD * WAVE + lane, &win[q], &wout[q]);
             // bit j of `in` / `out`: does this item enter / leave as anomalous at step sq + j
             const uint64_t in = gd_transpose64(wi, lane);
-            const uint64_t out = gd_transpose64(wo, lane);
+            uint64_t out;
+            if (RING > 0 && sq >= W) {               // (sq and W are multiples of 64)
+                const uint32_t n = T - sq;           // steps of the batch in this block
+                out = entered[q % (RING > 0 ? RING : 1)] & (n < 64 ? (1ull << n) - 1 : ~0ull);
+            }
+            else out = gd_transpose64(wo, lane);
+            if (RING > 0) entered[q % (RING > 0 ? RING : 1)] = in;
             const uint32_t pin = __popcll(in), pout = __popcll(out);
             if (f == 0 && c + pin >= K) {             // the flag may first rise inside this block
                 const uint32_t n = min((uint32_t)WAVE, T - sq);
@@ -139,7 +153,16 @@ __global__ __launch_bounds__(WIN_NT) void flags_kernel(const gd_flags_args a) {
 hipError_t gd_launch_window(const gd_window_args& a, hipStream_t s) {
     if (a.T == 0) return hipSuccess;
     const uint32_t blocks = (a.R + WIN_NT - 1) / WIN_NT + (a.N + WIN_NT - 1) / WIN_NT;
-    hipLaunchKernelGGL(window_kernel, dim3(blocks), dim3(WIN_NT), 0, s, a);
+    // batches longer than the window, whose length is a whole number of 64-step blocks
+    const uint32_t ring = a.W % 64 == 0 && a.T > a.W ? a.W / 64 : 0;
+    switch (ring) {
+        case 1: hipLaunchKernelGGL(window_kernel<1>, dim3(blocks), dim3(WIN_NT), 0, s, a); break;
+        case 2: hipLaunchKernelGGL(window_kernel<2>, dim3(blocks), dim3(WIN_NT), 0, s, a); break;
+        case 4: hipLaunchKernelGGL(window_kernel<4>, dim3(blocks), dim3(WIN_NT), 0, s, a); break;
+        case 8: hipLaunchKernelGGL(window_kernel<8>, dim3(blocks), dim3(WIN_NT), 0, s, a); break;
+        case 16: hipLaunchKernelGGL(window_kernel<16>, dim3(blocks), dim3(WIN_NT), 0, s, a); break;
+        default: hipLaunchKernelGGL(window_kernel<0>, dim3(blocks), dim3(WIN_NT), 0, s, a); break;
+    }
     return hipGetLastError();
 }
 

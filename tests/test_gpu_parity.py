@@ -445,3 +445,30 @@ def test_single_node_sweep_scoring(B):
         assert np.array_equal(got["verdict"].cpu().numpy(), want[3])
     say("  verdicts", np.bincount(want[3], minlength=4).tolist())
     det.close()
+
+
+@pytest.mark.parametrize("W,T,chunks", [(64, 65, [65]), (64, 300, [200, 100]), (128, 293, [293]),
+                                        (256, 700, [1, 699]), (512, 1100, [600, 500]),
+                                        (1024, 1030, [1030]), (192, 500, [500])])
+def test_windows_of_whole_64_step_blocks(W, T, chunks):
+    """Windows that are a whole number of 64-step blocks long take a route of their own in
+    the window kernel when the batch is longer than the window; batches that are not a
+    whole number of blocks, that start inside a window, and a length (192) without that
+    route are all checked against the oracle's re-summed windows."""
+    say(f"case window W={W} T={T} chunks={chunks}")
+    R, M = 2048, 1
+    g = torch.Generator().manual_seed(W + T)
+    x = torch.exp(0.02 * torch.randn((T, M, R), generator=g, dtype=torch.float64))
+    # ranks and nodes that are anomalous on and off, so that counts rise and fall
+    for i in range(40):
+        r = int(torch.randint(0, R, (1,), generator=g))
+        on = torch.rand(T, generator=g) < (0.2 + 0.02 * i)
+        x[on, 0, r] *= 1.5
+    for n in (3, 77, 200):
+        on = torch.rand(T, generator=g) < 0.6
+        x[on, 0, n * 8:(n + 1) * 8] *= 1.2
+    x = x.to(torch.float32)
+    p = oracle_params(R=R, M=M, W=W, k=max(1, W // 3), min_signals=1)
+    rep = run_and_compare(p, x, topk_k=16, chunks=chunks, label=f"W{W}", want_z=False)
+    say("  report", rep)
+    assert rep["rank_flags"] >= 1
