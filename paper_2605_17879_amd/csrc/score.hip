@@ -241,17 +241,31 @@ template <int NT, typename SH>
 __device__ __forceinline__ void rank_candidates(SH& sh, uint32_t tid, uint32_t cnt, uint32_t wa,
                                                 uint32_t wb) {
     const uint32_t lane = tid & (WAVE - 1), w = rfl(tid >> 6);
-    for (uint32_t i = w; i < cnt; i += NT / WAVE) {
-        const uint32_t c = sh.cand[i];
-        uint32_t r = 0;                      // wave-uniform: candidates ordered before candidate i
-        for (uint32_t j0 = 0; j0 < cnt; j0 += WAVE) {
-            const uint32_t j = j0 + lane;
-            const uint32_t cj = j < cnt ? sh.cand[j] : 0xFFFFFFFFu;
-            r += (uint32_t)__popcll(__ballot(j < cnt && (cj < c || (cj == c && j < i))));
+    if (cnt <= (uint32_t)WAVE) {
+        // one LDS read per wave: lane j holds candidate j, candidate i is read from lane i
+        // (read whatever the slot holds: the load then does not wait for cnt)
+        const uint32_t cj = sh.cand[lane];
+        for (uint32_t i = w; i < cnt; i += NT / WAVE) {
+            const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)cj, (int)i);
+            const uint32_t r = (uint32_t)__popcll(__ballot(lane < cnt && (cj < c || (cj == c && lane < i))));
+            if (lane == 0) {
+                if (r == wa) sh.res[4] = c;
+                if (r == wb) sh.res[5] = c;
+            }
         }
-        if (lane == 0) {
-            if (r == wa) sh.res[4] = c;
-            if (r == wb) sh.res[5] = c;
+    } else {
+        for (uint32_t i = w; i < cnt; i += NT / WAVE) {
+            const uint32_t c = sh.cand[i];
+            uint32_t r = 0;                      // wave-uniform: candidates ordered before candidate i
+            for (uint32_t j0 = 0; j0 < cnt; j0 += WAVE) {
+                const uint32_t j = j0 + lane;
+                const uint32_t cj = j < cnt ? sh.cand[j] : 0xFFFFFFFFu;
+                r += (uint32_t)__popcll(__ballot(j < cnt && (cj < c || (cj == c && j < i))));
+            }
+            if (lane == 0) {
+                if (r == wa) sh.res[4] = c;
+                if (r == wb) sh.res[5] = c;
+            }
         }
     }
     __syncthreads();
