@@ -472,3 +472,50 @@ def test_windows_of_whole_64_step_blocks(W, T, chunks):
     rep = run_and_compare(p, x, topk_k=16, chunks=chunks, label=f"W{W}", want_z=False)
     say("  report", rep)
     assert rep["rank_flags"] >= 1
+
+
+@pytest.mark.parametrize("R,T", [(256, 9000), (1024, 9000), (4096, 2400), (16384, 2400), (65536, 800)])
+def test_hinted_runs_under_regime_changes(R, T):
+    """Long enough batches that every workgroup scores several consecutive steps and
+    carries the previous step's median, reach and MAD over as hints -- on data whose
+    level, spread and character keep changing from one step to the next: level jumps,
+    spread collapsing to ties or exploding, two-valued and constant columns, signs,
+    missing samples, then calm again."""
+    say(f"case regime changes R={R} T={T}")
+    M = 2
+    g = torch.Generator().manual_seed(R // 7 + T)
+    level = torch.ones(T, dtype=torch.float64)
+    spread = torch.full((T,), 0.02, dtype=torch.float64)
+    kind = torch.zeros(T, dtype=torch.int64)
+    t = 0
+    while t < T:
+        run = int(torch.randint(1, 12, (1,), generator=g))
+        k = int(torch.randint(0, 10, (1,), generator=g))
+        lv = float(torch.exp(torch.randn(1, generator=g) * (3.0 if k == 1 else 0.05)))
+        sp = [0.02, 0.02, 2.0, 1e-6, 0.0, 0.02, 0.02, 0.02, 0.3, 0.02][k]
+        level[t:t + run] = lv
+        spread[t:t + run] = sp
+        kind[t:t + run] = k
+        t += run
+    x = level[:, None, None] * torch.exp(spread[:, None, None] *
+                                         torch.randn((T, M, R), generator=g, dtype=torch.float64))
+    x[:, 1] = 300.0 / x[:, 1]
+    for t in range(T):
+        k = int(kind[t])
+        if k == 5:                                   # two values
+            x[t, 0] = torch.where(torch.rand(R, generator=g, dtype=torch.float64) < 0.5, level[t], level[t] * 1.01)
+        elif k == 6:                                 # signs
+            x[t, 0, ::3] = -x[t, 0, ::3]
+        elif k == 7:                                 # missing samples
+            x[t, 0, torch.randperm(R, generator=g)[: max(1, R // 9)]] = NAN
+            x[t, 1, int(torch.randint(0, R, (1,), generator=g))] = NAN
+    x[:, :, 8:16] *= 1.15
+    x = x.to(torch.float32)
+    p = oracle_params(R=R, M=M, W=8, k=4, directions=(1, -1), min_signals=1)
+    det = detector_for(p)
+    det.set_streaming_steps(0)
+    out = gpu_score(det, x, want_z=False)
+    o = oracle.score(p, x.numpy(), want_z=False)
+    rep = compare_scores(o, out, "regime changes")
+    say("  report", rep)
+    det.close()
