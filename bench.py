@@ -108,6 +108,24 @@ def streaming_latency(torch, n_steps: int) -> dict:
             "p99_us": 1e6 * lat[int(len(lat) * 0.99)]}
 
 
+def detection_report(torch, det, w, x, out, fl) -> dict:
+    """What the detector says at the end of the batch against the faults the generator
+    injected (reported, not gated: small slowdowns are not detectable by design)."""
+    from workloads.telemetry import faults
+    torch.cuda.synchronize()
+    truth = sorted({f.rank_lo // w.G for f in faults(w, 3)})
+    flagged = torch.nonzero(fl["node_flag"] != 0).flatten().cpu().tolist()
+    hit = len(set(flagged) & set(truth))
+    sev = det.alloc_severity()
+    det.severity(x, out, sev)
+    torch.cuda.synchronize()
+    tiers = torch.bincount(sev["tier"].to(torch.int64), minlength=4).cpu().tolist()
+    return {"injected_slow_nodes": len(truth), "flagged_nodes": len(flagged), "true_positives": hit,
+            "recall": hit / max(1, len(truth)), "precision": hit / max(1, len(flagged)),
+            "nodes_per_severity_tier": {"not_flagged": tiers[0], "no_observable_impact": tiers[1],
+                                        "moderate": tiers[2], "severe": tiers[3]}}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -193,6 +211,7 @@ def main() -> int:
                      "read_only_ceiling": {"GB/s": x.numel() * 4 / (read_ms * 1e-3) / 1e9, "ms": read_ms,
                                            "what": "the same loads with no arithmetic (gd_probe_read)"}},
     }
+    res["detection"] = detection_report(torch, det, w, x, out, fl)
     if not a.no_cpu:
         res["cpu_baseline"] = cpu_baseline(w, x, a.cpu_sample_steps)
     del x, out
