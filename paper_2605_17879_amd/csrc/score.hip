@@ -707,7 +707,7 @@ __device__ __forceinline__ void score_row_decide(const float (&x)[4], float xsta
 // exceed bits of a column are then OR-ed into the (zeroed) mask outputs in global
 // memory and combine_kernel applies the multi-signal rule afterwards.
 template <int NT, int ROWS, int LOG_NB, bool FULL, bool SPLIT>
-__global__ __launch_bounds__(NT) void score_kernel(const gd_score_args a) {
+__global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {   // <= 128 VGPRs: 16 waves per CU
     constexpr int BLK = NT * 4;               // ranks per register row
     constexpr int MAX_NODES = BLK * ROWS / 8;
     constexpr int NWAVES = NT / WAVE;
@@ -1245,8 +1245,10 @@ hipError_t gd_launch_score(const gd_score_args& a, hipStream_t s) {
     const uint32_t R = a.R;
     if (R <= 256) return launch<64, 1, 10>(a, s);
     if (R <= 1024) return launch<64, 4, 10>(a, s);
-    if (R <= 4096) return launch<256, 4, 12>(a, s);
-    if (R <= 16384) return launch<256, 16, 12>(a, s);
+    // (the 256-thread tilings take 2048 buckets: four workgroups then share a CU's LDS, and
+    // their barrier-bound phases overlap)
+    if (R <= 4096) return launch<256, 4, 11>(a, s);
+    if (R <= 16384) return launch<256, 16, 11>(a, s);
     if (R <= 32768) return launch<512, 16, 12>(a, s);
     if (R <= 65536) return launch<1024, 16, 12>(a, s);
     return hipErrorInvalidValue;
