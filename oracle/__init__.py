@@ -81,6 +81,15 @@ def _load():
         _lib.go_severity.argtypes = [ctypes.POINTER(_Cfg), vp, ctypes.c_uint64, vp, vp,
                                      ctypes.c_float, ctypes.c_float, vp, vp]
         _lib.go_severity.restype = None
+        u32, u64 = ctypes.c_uint32, ctypes.c_uint64
+        _lib.go_metric_window.argtypes = [u32, u32, u32, vp, u64, u32, u32, vp, vp, vp, vp]
+        _lib.go_metric_window.restype = None
+        _lib.go_score_ring.argtypes = [u32, vp, u64, u32, ctypes.c_float, vp]
+        _lib.go_score_ring.restype = None
+        _lib.go_topk_mean.argtypes = [u32, vp, vp, u32, vp, vp]
+        _lib.go_topk_mean.restype = None
+        _lib.go_recurrence.argtypes = [u32, vp, u64, u64, u32, vp, vp]
+        _lib.go_recurrence.restype = None
     return _lib
 
 
@@ -263,6 +272,56 @@ def sweep(flops: np.ndarray, bw: np.ndarray, tol_compute: float = 0.05, tol_sym:
     _load().go_sweep(B, _ptr(flops), _ptr(bw), tol_compute, tol_sym, tol_bw, _ptr(sf), _ptr(gm),
                      _ptr(lm), _ptr(vd))
     return sf, gm, lm, vd
+
+
+@dataclass
+class MetricPersistence:
+    count: np.ndarray   # [8][n] u16 per-metric window counts at the last step
+    pmask: np.ndarray   # [n] u8, bit m = metric m persistent at the last step
+    flag: np.ndarray    # [n] u8 at the last step
+    first: np.ndarray   # [n] i32 first flagged step or -1
+
+
+def metric_window(mask: np.ndarray, primary: int, min_signals: int, W: int, k: int) -> MetricPersistence:
+    """Per-metric k-of-W persistence over the whole history of exceed bytes mask[T][n]."""
+    mask = np.ascontiguousarray(mask, np.uint8)
+    T, n = mask.shape
+    o = MetricPersistence(np.zeros((8, n), np.uint16), np.zeros(n, np.uint8), np.zeros(n, np.uint8),
+                          np.full(n, -1, np.int32))
+    _load().go_metric_window(n, primary, min_signals, _ptr(mask), T, W, k, _ptr(o.count),
+                             _ptr(o.pmask), _ptr(o.flag), _ptr(o.first))
+    return o
+
+
+def score_ring(node_z: np.ndarray, W: int, quant: float = 64.0) -> np.ndarray:
+    """sum[N] i32 of the quantised primary node scores over the last min(T, W) steps."""
+    node_z = np.ascontiguousarray(node_z, np.float32)
+    T, N = node_z.shape
+    out = np.zeros(N, np.int32)
+    _load().go_score_ring(N, _ptr(node_z), T, W, quant, _ptr(out))
+    return out
+
+
+def topk_mean(node_count: np.ndarray, score_sum: np.ndarray, k: int):
+    """(idx[k] i32, key[k] u64) of the k slowest nodes by (count, windowed score sum, index)."""
+    node_count = np.ascontiguousarray(node_count, np.uint16)
+    score_sum = np.ascontiguousarray(score_sum, np.int32)
+    N = node_count.shape[0]
+    assert score_sum.shape[0] == N and 0 <= k <= N and N <= 65536
+    idx = np.empty(k, np.int32)
+    key = np.empty(k, np.uint64)
+    _load().go_topk_mean(N, _ptr(node_count), _ptr(score_sum), k, _ptr(idx), _ptr(key))
+    return idx, key
+
+
+def recurrence(flag_hist: np.ndarray, horizon: int, limit: int = 3):
+    """(episodes[N] u8, terminal_first[N] i32) from the per-step node flags flag_hist[T][N]."""
+    flag_hist = np.ascontiguousarray(flag_hist, np.uint8)
+    T, N = flag_hist.shape
+    ep = np.zeros(N, np.uint8)
+    tf = np.full(N, -1, np.int32)
+    _load().go_recurrence(N, _ptr(flag_hist), T, horizon, limit, _ptr(ep), _ptr(tf))
+    return ep, tf
 
 
 def detect(p: Params, x: np.ndarray, topk_k: int, want_z: bool = False):

@@ -18,6 +18,11 @@
 //                                                          go_flags, go_topk
 //   * the response to a flagged node depends on how much it slows the job
 //     (none / about 10% / 20% or more)                  -> go_severity
+//   * each indicator sustained on its own, then combined  -> go_metric_window
+//   * ranking by the node score averaged over the window -> go_score_ring,
+//                                                          go_topk_mean
+//   * a node that keeps coming back to triage (three times within a week,
+//     Section 7) is terminally bad                      -> go_recurrence
 // The estimators and constants (median, MAD x 1.4826, threshold, k-of-W,
 // scaled node sum, ranking key) are this repository's stated reading of those
 // sentences; each function says which rule it implements.
@@ -382,6 +387,116 @@ void go_sweep(uint32_t n_nodes, const float* flops, const float* bw, float tol_c
         gpu_mask[b] = gm;
         link_mask[b] = lm;
         verdict[b] = (uint8_t)((gm ? 1 : 0) | (lm ? 2 : 0));
+    }
+}
+
+// Persistence kept per indicator (the other reading of "multiple performance
+// indicators ... sustained across consecutive evaluation windows", Section 4.2:
+// each indicator must itself be sustained, and the indicators are combined
+// afterwards).  mask is the full history [T][n] of exceed bytes (bit m = metric m
+// exceeds for that item at that step) from step 0.  For every item and step:
+//   c_m(t) = number of steps among the last W ending at t with bit m set
+//   p_m(t) = c_m(t) >= k
+//   flag(t) = p_primary(t)  and  (number of m with p_m(t)) >= min_signals
+//   count [8][n], pmask [n] (bit m = p_m), flag [n] : at the last step (0 if T == 0)
+//   first [n] : first step with flag, or -1
+void go_metric_window(uint32_t n, uint32_t primary, uint32_t min_signals, const uint8_t* mask,
+                      uint64_t T, uint32_t W, uint32_t k, uint16_t* count, uint8_t* pmask,
+                      uint8_t* flag, int32_t* first) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < (int64_t)n; ++i) {
+        int32_t f = -1;
+        uint32_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        uint8_t pm = 0, fl = 0;
+        for (uint64_t t = 0; t < T; ++t) {
+            const uint64_t lo = t + 1 >= W ? t + 1 - W : 0;
+            pm = 0;
+            uint32_t np = 0;
+            for (int m = 0; m < 8; ++m) {
+                c[m] = 0;
+                for (uint64_t u = lo; u <= t; ++u) c[m] += (mask[u * n + i] >> m) & 1u;
+                if (c[m] >= k) { pm |= (uint8_t)(1u << m); ++np; }
+            }
+            fl = ((pm >> primary) & 1u) && np >= min_signals ? 1 : 0;
+            if (fl && f < 0) f = (int32_t)t;
+        }
+        for (int m = 0; m < 8; ++m) count[(size_t)m * n + i] = (uint16_t)c[m];
+        pmask[i] = pm;
+        flag[i] = fl;
+        first[i] = f;
+    }
+}
+
+// Node score averaged over the window, for ranking: each step's primary node score
+// is quantised to an integer, q = clamp(round-half-even(node_z * quant), -32768, 32767)
+// (the product rounded to fp32 first; a NaN counts as 0), and
+//   sum[n] = q summed over the last min(T, W) steps of the history node_z[T][N].
+// All nodes share the divisor, so ordering by the sum is ordering by the mean; integer
+// sums do not depend on the order of addition.
+void go_score_ring(uint32_t N, const float* node_z, uint64_t T, uint32_t W, float quant,
+                   int32_t* sum) {
+    const uint64_t Ws = T < W ? T : W;
+    for (uint32_t n = 0; n < N; ++n) {
+        int32_t s = 0;
+        for (uint64_t t = T - Ws; t < T; ++t) {
+            const float v = node_z[t * N + n] * quant;
+            int32_t q = 0;
+            if (!std::isnan(v)) {
+                float r = std::nearbyintf(v);       // round to nearest, ties to even
+                if (r > 32767.0f) r = 32767.0f;
+                if (r < -32768.0f) r = -32768.0f;
+                q = (int32_t)r;
+            }
+            s += q;
+        }
+        sum[n] = s;
+    }
+}
+
+// Ranking by (persistence count, high first; windowed score sum, high first; node
+// index, low first), key = count << 48 | (sum + 2^31) << 16 | (0xFFFF - index).
+void go_topk_mean(uint32_t N, const uint16_t* node_count, const int32_t* sum, uint32_t k,
+                  int32_t* idx, uint64_t* key) {
+    std::vector<uint32_t> order(N);
+    for (uint32_t n = 0; n < N; ++n) order[n] = n;
+    std::sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
+        if (node_count[a] != node_count[b]) return node_count[a] > node_count[b];
+        if (sum[a] != sum[b]) return sum[a] > sum[b];
+        return a < b;
+    });
+    for (uint32_t j = 0; j < k && j < N; ++j) {
+        const uint32_t n = order[j];
+        idx[j] = (int32_t)n;
+        const uint32_t biased = (uint32_t)((int64_t)sum[n] + 2147483648ll);
+        key[j] = ((uint64_t)node_count[n] << 48) | ((uint64_t)biased << 16) | (uint64_t)(0xFFFFu - n);
+    }
+}
+
+// Recurrence (Section 7, triage: a node sent to triage `limit` times within a
+// period -- three times within a week in the paper's clusters -- is taken to be
+// terminally bad).  flag_hist[T][N] is the node persistence flag of every step from
+// step 0.  An episode starts at step t when flag(t) is set and flag(t-1) is not
+// (nothing is set before step 0).  For every step,
+//   e(t) = number of episode starts s with t - horizon < s <= t;
+//   terminal_first[n] = first t with e(t) >= limit, or -1;
+//   episodes[n] = min(e(T-1), limit)   (0 if T == 0).
+void go_recurrence(uint32_t N, const uint8_t* flag_hist, uint64_t T, uint64_t horizon, uint32_t limit,
+                   uint8_t* episodes, int32_t* terminal_first) {
+    for (uint32_t n = 0; n < N; ++n) {
+        std::vector<uint64_t> starts;
+        int32_t tf = -1;
+        uint32_t e = 0;
+        for (uint64_t t = 0; t < T; ++t) {
+            const bool now = flag_hist[t * N + n] != 0;
+            const bool before = t > 0 && flag_hist[(t - 1) * N + n] != 0;
+            if (now && !before) starts.push_back(t);
+            e = 0;
+            for (uint64_t s : starts)
+                if (s + horizon > t) ++e;
+            if (e >= limit && tf < 0) tf = (int32_t)t;
+        }
+        episodes[n] = (uint8_t)(e < limit ? e : limit);
+        terminal_first[n] = tf;
     }
 }
 
