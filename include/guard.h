@@ -231,6 +231,84 @@ gd_status gd_sweep_score(gd_handle h, const float* d_flops, const float* d_bw, u
                          uint8_t* d_gpu_mask, uint32_t* d_link_mask, uint8_t* d_verdict, void* stream);
 
 /*
+ * The ledger: bookkeeping beyond the default rule, in a buffer of its own.
+ *
+ *  - Persistence per indicator, the other reading of Section 4.2's "multiple
+ *    performance indicators ... sustained across consecutive evaluation windows":
+ *    each metric keeps its own count of exceeding steps among the last `window`, a
+ *    metric is sustained when that count has reached persist_k, and an item (a rank
+ *    or a node) is flagged when the primary metric is sustained and at least
+ *    min_signals metrics are.  (The default rule combines the metrics of each step
+ *    first and persists the result.)
+ *  - The primary node score summed over the window in integers,
+ *    q = clamp(round-half-even(node_z * score_quant), -32768, 32767), NaN -> 0, for a
+ *    ranking by the score averaged over the window rather than the latest one.
+ *  - Recurrence (Section 7: a node sent to triage three times within a week is
+ *    taken to be terminally bad): an episode starts at a step where the node's
+ *    default-rule flag (its combined anomaly bit, k of W) rises; a node is terminal
+ *    from the first step at which recur_limit episodes began within the last
+ *    recur_horizon steps.
+ */
+typedef struct gd_ledger_config {
+    uint32_t struct_size;    /* = sizeof(gd_ledger_config)                                   */
+    float    score_quant;    /* finite, > 0; 64 keeps 1/64 of a score unit, range -512..512  */
+    uint32_t recur_limit;    /* 1..8; the paper's clusters used 3                            */
+    uint32_t reserved;       /* 0                                                            */
+    uint64_t recur_horizon;  /* steps, >= 1: "a week" in evaluation steps                    */
+} gd_ledger_config;
+
+/* Fills c with score_quant 64, recur_limit 3, recur_horizon 604800 (a week of one-second steps). */
+void gd_default_ledger_config(gd_ledger_config* c);
+
+/* Bytes of the ledger for batches of at most max_T steps (0 for a null handle). */
+size_t gd_ledger_bytes(gd_handle h, uint32_t max_T);
+
+/*
+ * Binds a caller-owned, 256-byte aligned device buffer of at least
+ * gd_ledger_bytes(h, max_T) bytes.  All zero bytes are a fresh ledger; the bytes
+ * are position-independent (a checkpoint is a copy).  The handle keeps cfg by value.
+ */
+gd_status gd_bind_ledger(gd_handle h, const gd_ledger_config* cfg, void* d_ledger, size_t bytes,
+                         uint32_t max_T);
+
+/*
+ * Takes the T steps gd_score_batch just scored into the ledger.
+ *   d_exceed_mask [T][R] u8, d_node_mask [T][N] u8, d_node_z [T][N] f32: its outputs
+ *   first_step_index: index of the batch's first step; batches must arrive in order
+ *                     and first_step_index + T must stay below 2^31
+ * T == 0 is GD_OK and does nothing; T > max_T is GD_ERR_INVALID_ARG.  Independent of
+ * gd_update_window: either may be called without the other, in any order.
+ */
+gd_status gd_update_ledger(gd_handle h, const uint8_t* d_exceed_mask, const uint8_t* d_node_mask,
+                           const float* d_node_z, uint32_t T, uint64_t first_step_index,
+                           void* stream);
+
+/*
+ * Reads the ledger as of the last step taken in.  Every output is device memory
+ * and may be NULL.
+ *   d_rank_pmask [R] u8   bit m: metric m is sustained for the rank
+ *   d_rank_pflag [R] u8   1 when the per-indicator rule flags the rank now
+ *   d_rank_pfirst [R] i32 first step at which it did, -1 = never
+ *   d_node_pmask, d_node_pflag, d_node_pfirst [N]: the same for nodes
+ *   d_node_score_sum [N] i32  sum of q over the last min(steps so far, window) steps
+ *   d_node_episodes [N] u8    episodes begun within the last recur_horizon steps,
+ *                             saturating at recur_limit
+ *   d_node_terminal_first [N] i32  first step at which the node was terminal, -1 = never
+ */
+gd_status gd_ledger_flags(gd_handle h, uint8_t* d_rank_pmask, uint8_t* d_rank_pflag,
+                          int32_t* d_rank_pfirst, uint8_t* d_node_pmask, uint8_t* d_node_pflag,
+                          int32_t* d_node_pfirst, int32_t* d_node_score_sum,
+                          uint8_t* d_node_episodes, int32_t* d_node_terminal_first, void* stream);
+
+/*
+ * The k slowest nodes by (window count of the default rule as the ledger keeps it,
+ * high first; windowed score sum, high first; node index, low first).
+ *   d_idx [k] i32; d_key [k] u64 = count << 48 | (sum + 2^31) << 16 | (0xFFFF - index), or NULL
+ * k == 0 selects the configured default; k > N is GD_ERR_INVALID_ARG.
+ */
+gd_status gd_topk_nodes_mean(gd_handle h, uint32_t k, int32_t* d_idx, uint64_t* d_key, void* stream);
+
+/*
  * Diagnostic for benchmarks: reads the first n_bytes (rounded down to a multiple of
  * 256 KiB) of d_x with the scoring kernel's own load pattern and does nothing else,
  * so that its duration next to gd_score_batch's gives the ceiling of a single pass

@@ -17,6 +17,10 @@ struct gd_handle_s {
     gd_state_layout lay;
     uint8_t* d_state;
     uint32_t split_steps;
+    gd_ledger_config lcfg;
+    gd_ledger_layout llay;
+    uint8_t* d_led;
+    uint32_t led_max_T;
     std::string err;
 };
 
@@ -37,6 +41,29 @@ gd_state_layout make_layout(uint32_t R, uint32_t N, uint32_t W) {
     l.rank_first = o;  o = align256(o + (size_t)R * 4);
     l.node_first = o;  o = align256(o + (size_t)N * 4);
     l.node_z_last = o; o = align256(o + (size_t)N * 4);
+    l.total = o;
+    return l;
+}
+
+gd_ledger_layout make_ledger_layout(uint32_t R, uint32_t N, uint32_t W, uint32_t max_T) {
+    const size_t NW = (N + 63) / 64;
+    gd_ledger_layout l;
+    size_t o = 0;
+    l.head = o;        o = align256(o + 32);
+    l.rank_ring = o;   o = align256(o + (size_t)W * R);
+    l.node_ring = o;   o = align256(o + (size_t)W * N);
+    l.rank_cnt = o;    o = align256(o + (size_t)R * 16);
+    l.node_cnt = o;    o = align256(o + (size_t)N * 16);
+    l.node_ccnt = o;   o = align256(o + (size_t)N * 2);
+    l.counts_bytes = o - l.rank_cnt;
+    l.counts_new = o;  o += l.counts_bytes;
+    l.rank_first = o;  o = align256(o + (size_t)R * 4);
+    l.node_first = o;  o = align256(o + (size_t)N * 4);
+    l.node_qring = o;  o = align256(o + (size_t)W * N * 2);
+    l.node_qsum = o;   o = align256(o + (size_t)N * 4);
+    l.node_starts = o; o = align256(o + (size_t)N * 32);
+    l.node_term = o;   o = align256(o + (size_t)N * 4);
+    l.rise = o;        o = align256(o + (size_t)max_T * NW * 8);
     l.total = o;
     return l;
 }
@@ -117,6 +144,8 @@ gd_status gd_create(const gd_config* c, gd_handle* out) {
     h->lay = make_layout(c->n_ranks, N, c->window);
     h->d_state = nullptr;
     h->split_steps = GD_DEFAULT_STREAMING_STEPS;
+    h->d_led = nullptr;
+    h->led_max_T = 0;
     *out = h;
     return GD_OK;
 }
@@ -225,7 +254,10 @@ gd_status gd_topk_nodes(gd_handle h, uint32_t k, int32_t* d_idx, uint64_t* d_key
     if (((uintptr_t)d_idx & 3) || ((uintptr_t)d_key & 7))
         return fail(h, GD_ERR_INVALID_ARG, "gd_topk_nodes: misaligned pointer");
     gd_topk_args a;
-    a.state = h->d_state; a.lay = h->lay; a.idx = d_idx; a.key = d_key; a.N = h->N; a.k = k;
+    a.count = reinterpret_cast<const uint16_t*>(h->d_state + h->lay.node_count);
+    a.z_last = reinterpret_cast<const float*>(h->d_state + h->lay.node_z_last);
+    a.score_sum = nullptr;
+    a.idx = d_idx; a.key = d_key; a.N = h->N; a.k = k;
     hipError_t e = gd_launch_topk(a, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(h, e, "gd_topk_nodes");
     return GD_OK;
@@ -269,6 +301,116 @@ gd_status gd_sweep_score(gd_handle h, const float* d_flops, const float* d_bw, u
     a.tol_compute = tol_compute; a.tol_sym = tol_sym; a.tol_bw = tol_bw;
     hipError_t e = gd_launch_sweep(a, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(h, e, "gd_sweep_score");
+    return GD_OK;
+}
+
+void gd_default_ledger_config(gd_ledger_config* c) {
+    if (!c) return;
+    memset(c, 0, sizeof(*c));
+    c->struct_size = (uint32_t)sizeof(gd_ledger_config);
+    c->score_quant = 64.0f;
+    c->recur_limit = 3;
+    c->recur_horizon = 604800;
+}
+
+size_t gd_ledger_bytes(gd_handle h, uint32_t max_T) {
+    return h ? make_ledger_layout(h->cfg.n_ranks, h->N, h->cfg.window, max_T).total : 0;
+}
+
+gd_status gd_bind_ledger(gd_handle h, const gd_ledger_config* cfg, void* d_ledger, size_t bytes,
+                         uint32_t max_T) {
+    if (!h) return GD_ERR_INVALID_ARG;
+    if (!cfg || !d_ledger) return fail(h, GD_ERR_INVALID_ARG, "gd_bind_ledger: null argument");
+    if (cfg->struct_size != sizeof(gd_ledger_config))
+        return fail(h, GD_ERR_BAD_CONFIG, "struct_size does not match this library's gd_ledger_config");
+    if (!isfinite(cfg->score_quant) || !(cfg->score_quant > 0.0f))
+        return fail(h, GD_ERR_BAD_CONFIG, "score_quant must be finite and positive");
+    if (cfg->recur_limit < 1 || cfg->recur_limit > 8)
+        return fail(h, GD_ERR_BAD_CONFIG, "recur_limit must be 1..8");
+    if (cfg->recur_horizon < 1 || cfg->recur_horizon > (1ull << 62))
+        return fail(h, GD_ERR_BAD_CONFIG, "recur_horizon must be 1..2^62 steps");
+    if (max_T < 1) return fail(h, GD_ERR_INVALID_ARG, "gd_bind_ledger: max_T must be at least 1");
+    if (((uintptr_t)d_ledger & 255) != 0)
+        return fail(h, GD_ERR_INVALID_ARG, "gd_bind_ledger: ledger must be 256-byte aligned");
+    const gd_ledger_layout l = make_ledger_layout(h->cfg.n_ranks, h->N, h->cfg.window, max_T);
+    if (bytes < l.total)
+        return fail(h, GD_ERR_BUFFER_TOO_SMALL, "gd_bind_ledger: buffer smaller than gd_ledger_bytes");
+    h->lcfg = *cfg;
+    h->llay = l;
+    h->d_led = static_cast<uint8_t*>(d_ledger);
+    h->led_max_T = max_T;
+    return GD_OK;
+}
+
+gd_status gd_update_ledger(gd_handle h, const uint8_t* d_exceed_mask, const uint8_t* d_node_mask,
+                           const float* d_node_z, uint32_t T, uint64_t first_step_index,
+                           void* stream) {
+    if (!h) return GD_ERR_INVALID_ARG;
+    if (!h->d_led) return fail(h, GD_ERR_INVALID_ARG, "gd_update_ledger: no ledger bound");
+    if (T == 0) return GD_OK;
+    if (T > h->led_max_T)
+        return fail(h, GD_ERR_INVALID_ARG, "gd_update_ledger: T exceeds the max_T the ledger was bound with");
+    if (!d_exceed_mask || !d_node_mask || !d_node_z)
+        return fail(h, GD_ERR_INVALID_ARG, "gd_update_ledger: a required pointer is null");
+    if (((uintptr_t)d_exceed_mask & 3) || ((uintptr_t)d_node_z & 3))
+        return fail(h, GD_ERR_INVALID_ARG, "gd_update_ledger: misaligned pointer");
+    if (first_step_index + (uint64_t)T > 0x7FFFFFFFull)
+        return fail(h, GD_ERR_INVALID_ARG, "gd_update_ledger: step index beyond 2^31 - 1");
+    gd_ledger_args a;
+    a.led = h->d_led; a.lay = h->llay;
+    a.exceed_mask = d_exceed_mask; a.node_mask = d_node_mask; a.node_z = d_node_z;
+    a.T = T; a.R = h->cfg.n_ranks; a.N = h->N; a.W = h->cfg.window; a.K = h->cfg.persist_k;
+    a.primary = h->cfg.primary_metric; a.min_signals = h->cfg.min_signals;
+    // a chunk rebuilds its starting counts from the W steps before it: keep that a
+    // quarter of its own length at most
+    a.chunk = 4 * h->cfg.window < 256 ? 256 : 4 * h->cfg.window;
+    a.limit = h->lcfg.recur_limit;
+    a.quant = h->lcfg.score_quant;
+    a.first_step = first_step_index; a.horizon = h->lcfg.recur_horizon;
+    hipError_t e = gd_launch_ledger(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(h, e, "gd_update_ledger");
+    return GD_OK;
+}
+
+gd_status gd_ledger_flags(gd_handle h, uint8_t* d_rank_pmask, uint8_t* d_rank_pflag,
+                          int32_t* d_rank_pfirst, uint8_t* d_node_pmask, uint8_t* d_node_pflag,
+                          int32_t* d_node_pfirst, int32_t* d_node_score_sum,
+                          uint8_t* d_node_episodes, int32_t* d_node_terminal_first, void* stream) {
+    if (!h) return GD_ERR_INVALID_ARG;
+    if (!h->d_led) return fail(h, GD_ERR_INVALID_ARG, "gd_ledger_flags: no ledger bound");
+    if (((uintptr_t)d_rank_pfirst & 3) || ((uintptr_t)d_node_pfirst & 3) ||
+        ((uintptr_t)d_node_score_sum & 3) || ((uintptr_t)d_node_terminal_first & 3))
+        return fail(h, GD_ERR_INVALID_ARG, "gd_ledger_flags: misaligned pointer");
+    gd_ledger_flags_args a;
+    a.led = h->d_led; a.lay = h->llay;
+    a.rank_pmask = d_rank_pmask; a.rank_pflag = d_rank_pflag; a.rank_pfirst = d_rank_pfirst;
+    a.node_pmask = d_node_pmask; a.node_pflag = d_node_pflag; a.node_pfirst = d_node_pfirst;
+    a.node_score_sum = d_node_score_sum; a.node_episodes = d_node_episodes;
+    a.node_terminal_first = d_node_terminal_first;
+    a.R = h->cfg.n_ranks; a.N = h->N; a.K = h->cfg.persist_k;
+    a.primary = h->cfg.primary_metric; a.min_signals = h->cfg.min_signals;
+    a.limit = h->lcfg.recur_limit; a.horizon = h->lcfg.recur_horizon;
+    hipError_t e = gd_launch_ledger_flags(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(h, e, "gd_ledger_flags");
+    return GD_OK;
+}
+
+gd_status gd_topk_nodes_mean(gd_handle h, uint32_t k, int32_t* d_idx, uint64_t* d_key, void* stream) {
+    if (!h) return GD_ERR_INVALID_ARG;
+    if (!h->d_led) return fail(h, GD_ERR_INVALID_ARG, "gd_topk_nodes_mean: no ledger bound");
+    if (k == 0) k = h->cfg.topk;
+    if (k == 0) return GD_OK;
+    if (k > h->N) return fail(h, GD_ERR_INVALID_ARG, "gd_topk_nodes_mean: k exceeds the number of nodes");
+    if (!d_idx) return fail(h, GD_ERR_INVALID_ARG, "gd_topk_nodes_mean: null index output");
+    if (((uintptr_t)d_idx & 3) || ((uintptr_t)d_key & 7))
+        return fail(h, GD_ERR_INVALID_ARG, "gd_topk_nodes_mean: misaligned pointer");
+    gd_topk_args a;
+    a.count = reinterpret_cast<const uint16_t*>(h->d_led + h->llay.node_ccnt);
+    a.z_last = nullptr;
+    a.score_sum = reinterpret_cast<const int32_t*>(h->d_led + h->llay.node_qsum);
+    a.idx = d_idx; a.key = d_key; a.N = h->N; a.k = k;
+    hipError_t e = gd_launch_topk(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(h, e, "gd_topk_nodes_mean");
     return GD_OK;
 }
 

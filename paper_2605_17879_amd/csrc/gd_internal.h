@@ -63,11 +63,60 @@ struct gd_flags_args {
 };
 
 struct gd_topk_args {
-    const uint8_t* state;
-    gd_state_layout lay;
+    const uint16_t* count;   // [N] window counts
+    const float* z_last;     // [N] latest primary node score, or null:
+    const int32_t* score_sum;  // [N] windowed sum of quantised node scores (used when z_last is null)
     int32_t* idx;   // [k]
     uint64_t* key;  // [k] or null
     uint32_t N, k;
+};
+
+// The ledger: bookkeeping beyond the default rule (persistence per indicator, the
+// node score summed over the window, recurrence of flag episodes).  Byte offsets
+// into the caller's ledger buffer, each a multiple of 256; zero bytes are a fresh
+// ledger.
+struct gd_ledger_layout {
+    size_t head;         // u64 [4]      [0] = index of the step after the last one taken in
+    size_t rank_ring;    // u8  [W][R]   exceed bytes of the last W steps, slot = step % W
+    size_t node_ring;    // u8  [W][N]
+    size_t rank_cnt;     // u16 [8][R]   per-metric window counts             } one span,
+    size_t node_cnt;     // u16 [8][N]                                        } counts_bytes
+    size_t node_ccnt;    // u16 [N]      window count of the per-step combined node anomaly  } long
+    size_t counts_new;   // the same span again: where a batch cut into chunks leaves its final counts
+    size_t counts_bytes;
+    size_t rank_first;   // u32 [R]      0xFFFFFFFF - first flagged step, 0 = never
+    size_t node_first;   // u32 [N]
+    size_t node_qring;   // i16 [W][N]   quantised primary node scores of the last W steps
+    size_t node_qsum;    // i32 [N]      their sum
+    size_t node_starts;  // i32 [8][N]   the latest episode starts (step + 1, 0 = none), newest first
+    size_t node_term;    // i32 [N]      first step with `limit` episodes inside the horizon, + 1
+    size_t rise;         // u64 [max_T][NW]  work area: episode starts found in the batch
+    size_t total;
+};
+
+struct gd_ledger_args {
+    uint8_t* led;
+    gd_ledger_layout lay;
+    const uint8_t* exceed_mask;   // [T][R]
+    const uint8_t* node_mask;     // [T][N]
+    const float* node_z;          // [T][N]
+    uint32_t T, R, N, W, K, primary, min_signals;
+    uint32_t chunk;               // steps per workgroup row of the counting kernel
+    uint32_t limit;               // episodes that make a node terminal (1..8)
+    float quant;
+    uint64_t first_step, horizon;
+};
+
+struct gd_ledger_flags_args {
+    const uint8_t* led;
+    gd_ledger_layout lay;
+    uint8_t* rank_pmask;  uint8_t* rank_pflag;  int32_t* rank_pfirst;
+    uint8_t* node_pmask;  uint8_t* node_pflag;  int32_t* node_pfirst;
+    int32_t* node_score_sum;
+    uint8_t* node_episodes;
+    int32_t* node_terminal_first;
+    uint32_t R, N, K, primary, min_signals, limit;
+    uint64_t horizon;
 };
 
 struct gd_severity_args {
@@ -100,5 +149,7 @@ hipError_t gd_launch_read_probe(const float* d_x, uint64_t n_bytes, uint32_t* d_
 hipError_t gd_launch_window(const gd_window_args& a, hipStream_t s);
 hipError_t gd_launch_flags(const gd_flags_args& a, hipStream_t s);
 hipError_t gd_launch_topk(const gd_topk_args& a, hipStream_t s);
+hipError_t gd_launch_ledger(const gd_ledger_args& a, hipStream_t s);
+hipError_t gd_launch_ledger_flags(const gd_ledger_flags_args& a, hipStream_t s);
 
 #endif  // GD_INTERNAL_H_

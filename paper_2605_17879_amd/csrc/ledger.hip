@@ -1,0 +1,319 @@
+// The ledger: bookkeeping beyond the default decision rule.
+//
+//  * Persistence per indicator -- the other reading of "multiple performance
+//    indicators ... sustained across consecutive evaluation windows" (Section 4.2):
+//    every metric keeps its own k-of-W count per rank and per node, and the
+//    multi-signal rule (primary among them, at least min_signals) is applied to
+//    the metrics that are themselves sustained.
+//  * The primary node score summed over the window as 16-bit integers, the key of
+//    the ranking "by average score" (integer sums do not depend on the order of
+//    addition, so the ring can be updated in any order).
+//  * Recurrence: how many flag episodes of a node began within a horizon (a node
+//    sent to triage three times within a week is terminally bad, Section 7).
+//
+// ledger_count_kernel: one thread per item (a rank or a node) and per chunk of
+// steps.  The per-metric counts live in four registers as eight 16-bit fields; a
+// step whose entering and leaving exceed bytes are equal (nearly all are) costs
+// two byte loads and a compare.  A chunk other than the first rebuilds its
+// starting counts from the W steps before it, so chunks are independent; the
+// first flagged step is the minimum over chunks (an atomic max on 0xFFFFFFFF -
+// step).  For nodes the kernel also follows the default rule's own flag and
+// leaves one bit per (step, node) where an episode starts.
+// ledger_finish_kernel, launched behind it: the rings take the batch's last
+// steps, the score sums are brought up to date, and one thread per node walks the
+// episode starts in step order.
+#include "gd_internal.h"
+
+namespace {
+
+constexpr int WAVE = 64;
+constexpr int LED_NT = 256;
+constexpr int LED_AHEAD = 8;     // steps whose bytes are fetched together
+constexpr int MAX_STARTS = 8;
+
+// bits 2j and 2j+1 of an exceed byte as the two 16-bit fields of a word
+__device__ __forceinline__ uint32_t spread2(uint32_t b, int j) {
+    const uint32_t v = (b >> (2 * j)) & 3u;
+    return (v | (v << 15)) & 0x00010001u;
+}
+
+// bit m set iff the count of metric m has reached K (counts <= 1024 < 0x8000 - K)
+__device__ __forceinline__ uint32_t sustained(const uint32_t (&c)[4], uint32_t K) {
+    const uint32_t bias = (0x8000u - K) * 0x00010001u;
+    uint32_t pm = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t t = c[j] + bias;
+        pm |= ((t >> 15) & 1u) << (2 * j);
+        pm |= ((t >> 31) & 1u) << (2 * j + 1);
+    }
+    return pm;
+}
+
+// the multi-signal rule on a byte of metric bits
+__device__ __forceinline__ uint32_t combine(uint32_t bits, uint32_t primary, uint32_t min_signals) {
+    return ((bits >> primary) & 1u) && (uint32_t)__popc(bits) >= min_signals ? 1u : 0u;
+}
+
+template <bool NODE>
+__device__ __forceinline__ void count_items(const gd_ledger_args& a, uint32_t blk) {
+    const uint32_t n_items = NODE ? a.N : a.R;
+    const uint32_t item = blk * LED_NT + threadIdx.x;
+    const uint32_t lane = threadIdx.x & (WAVE - 1);
+    if (item - lane >= n_items) return;                     // whole wave out of range
+    const bool live = item < n_items;
+    const uint32_t i = live ? item : n_items - 1;           // idle lanes repeat the last item, store nothing
+    const uint8_t* mask = NODE ? a.node_mask : a.exceed_mask;
+    const uint8_t* ring = a.led + (NODE ? a.lay.node_ring : a.lay.rank_ring);
+    uint16_t* cnt = reinterpret_cast<uint16_t*>(a.led + (NODE ? a.lay.node_cnt : a.lay.rank_cnt));
+    uint32_t* first = reinterpret_cast<uint32_t*>(a.led + (NODE ? a.lay.node_first : a.lay.rank_first));
+    uint16_t* ccnt = reinterpret_cast<uint16_t*>(a.led + a.lay.node_ccnt);
+    uint64_t* rise = reinterpret_cast<uint64_t*>(a.led + a.lay.rise);
+    const uint32_t W = a.W, K = a.K, T = a.T;
+    const uint32_t NW = (a.N + 63) / 64;
+    const uint32_t s0 = blockIdx.y * a.chunk;
+    const uint32_t s1 = min(T, s0 + a.chunk);
+    if (s0 >= s1) return;
+
+    // the exceed byte of step s of the batch; s < 0 reaches back into the ring
+    auto hist = [&](int64_t s) -> uint32_t {
+        if (s >= 0) return mask[(size_t)s * n_items + i];
+        const int64_t g = (int64_t)a.first_step + s;
+        return g >= 0 ? ring[(size_t)(g % W) * n_items + i] : 0u;
+    };
+
+    uint32_t c[4] = {0, 0, 0, 0};
+    uint32_t cc = 0;                                        // the default rule's count (nodes)
+    if (s0 == 0) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            c[j] = (uint32_t)cnt[(size_t)(2 * j) * n_items + i] |
+                   ((uint32_t)cnt[(size_t)(2 * j + 1) * n_items + i] << 16);
+        if (NODE) cc = ccnt[i];
+    } else {
+        for (int64_t s = (int64_t)s0 - W; s < (int64_t)s0; ++s) {
+            const uint32_t b = hist(s);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) c[j] += spread2(b, j);
+            if (NODE) cc += combine(b, a.primary, a.min_signals);
+        }
+    }
+    uint32_t pflag = combine(sustained(c, K), a.primary, a.min_signals);
+    uint32_t best = 0;                                      // 0xFFFFFFFF - first flagged step of the chunk
+    bool cflag = NODE && cc >= K;                           // the default rule's flag one step earlier
+
+    for (uint32_t s = s0; s < s1; s += LED_AHEAD) {
+        uint32_t eb[LED_AHEAD], lb[LED_AHEAD];
+#pragma unroll
+        for (int q = 0; q < LED_AHEAD; ++q) {
+            eb[q] = 0; lb[q] = 0;
+            if (s + q < s1) {
+                eb[q] = mask[(size_t)(s + q) * n_items + i];
+                lb[q] = hist((int64_t)(s + q) - W);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < LED_AHEAD; ++q) {
+            if (s + q >= s1) break;                         // uniform over the wave
+            const uint32_t e = eb[q], l = lb[q];
+            if (e != l) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) c[j] = c[j] + spread2(e, j) - spread2(l, j);
+                pflag = combine(sustained(c, K), a.primary, a.min_signals);
+                if (NODE) cc = cc + combine(e, a.primary, a.min_signals) - combine(l, a.primary, a.min_signals);
+            }
+            if (pflag && !best) best = 0xFFFFFFFFu - (uint32_t)(a.first_step + s + q);
+            if (NODE) {
+                const bool now = cc >= K;
+                const uint64_t rb = __ballot(live && now && !cflag);
+                cflag = now;
+                if (lane == 0) rise[(size_t)(s + q) * NW + item / 64] = rb;
+            }
+        }
+    }
+    if (!live) return;
+    if (best) atomicMax(&first[i], best);
+    if (s1 == T) {
+        // With several chunks the first one may still have to read the old counts:
+        // the new ones go to the staging span and the finishing kernel moves them.
+        const size_t shift = gridDim.y > 1 ? (a.lay.counts_new - a.lay.rank_cnt) / 2 : 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            cnt[shift + (size_t)(2 * j) * n_items + i] = (uint16_t)(c[j] & 0xFFFFu);
+            cnt[shift + (size_t)(2 * j + 1) * n_items + i] = (uint16_t)(c[j] >> 16);
+        }
+        if (NODE) ccnt[shift + i] = (uint16_t)cc;
+    }
+}
+
+// Blocks [0, rank_blocks) take ranks, the rest nodes; blockIdx.y is the chunk.
+__global__ __launch_bounds__(LED_NT) void ledger_count_kernel(const gd_ledger_args a) {
+    const uint32_t rank_blocks = (a.R + LED_NT - 1) / LED_NT;
+    if (blockIdx.x < rank_blocks) count_items<false>(a, blockIdx.x);
+    else count_items<true>(a, blockIdx.x - rank_blocks);
+}
+
+__device__ __forceinline__ int32_t quantise(float z, float quant) {
+    const float v = z * quant;
+    float r = __builtin_rintf(v);                           // ties to even
+    r = fminf(fmaxf(r, -32768.0f), 32767.0f);
+    return v == v ? (int32_t)r : 0;                         // a NaN counts as 0
+}
+
+// Blocks [0, node_blocks): one thread per node -- score ring and sum, then the
+// episode starts in step order.  Blocks after them copy the batch's last
+// min(T, W) exceed bytes into the rings, grid-stride.
+__global__ __launch_bounds__(LED_NT) void ledger_finish_kernel(const gd_ledger_args a) {
+    const uint32_t node_blocks = (a.N + LED_NT - 1) / LED_NT;
+    const uint32_t W = a.W, T = a.T, N = a.N, R = a.R;
+    const uint32_t keep = T < W ? T : W;
+    if (blockIdx.x >= node_blocks) {
+        uint8_t* rring = a.led + a.lay.rank_ring;
+        uint8_t* nring = a.led + a.lay.node_ring;
+        const size_t stride = (size_t)(gridDim.x - node_blocks) * LED_NT;
+        const size_t me = (size_t)(blockIdx.x - node_blocks) * LED_NT + threadIdx.x;
+        // ranks four at a time (R is a multiple of 8 and both arrays are word-aligned)
+        const size_t rwords = (size_t)keep * (R / 4);
+        for (size_t q = me; q < rwords; q += stride) {
+            const uint32_t s = T - keep + (uint32_t)(q / (R / 4));
+            const uint32_t r4 = (uint32_t)(q % (R / 4));
+            const uint32_t v = reinterpret_cast<const uint32_t*>(a.exceed_mask + (size_t)s * R)[r4];
+            reinterpret_cast<uint32_t*>(rring + (size_t)((a.first_step + s) % W) * R)[r4] = v;
+        }
+        const size_t nbytes = (size_t)keep * N;
+        for (size_t q = me; q < nbytes; q += stride) {
+            const uint32_t s = T - keep + (uint32_t)(q / N);
+            const uint32_t n = (uint32_t)(q % N);
+            nring[(size_t)((a.first_step + s) % W) * N + n] = a.node_mask[(size_t)s * N + n];
+        }
+        if (T > a.chunk) {       // the batch was cut into chunks: its final counts wait in the staging span
+            const uint32_t* from = reinterpret_cast<const uint32_t*>(a.led + a.lay.counts_new);
+            uint32_t* to = reinterpret_cast<uint32_t*>(a.led + a.lay.rank_cnt);
+            for (size_t q = me; q < a.lay.counts_bytes / 4; q += stride) to[q] = from[q];
+        }
+        return;
+    }
+    const uint32_t n = blockIdx.x * LED_NT + threadIdx.x;
+    const uint32_t lane = threadIdx.x & (WAVE - 1);
+    if (n - lane >= N) return;
+    const bool live = n < N;
+    const uint32_t i = live ? n : N - 1;
+    if (n == 0) reinterpret_cast<uint64_t*>(a.led + a.lay.head)[0] = a.first_step + T;
+
+    // score ring and sum
+    int16_t* qring = reinterpret_cast<int16_t*>(a.led + a.lay.node_qring);
+    int32_t* qsum = reinterpret_cast<int32_t*>(a.led + a.lay.node_qsum);
+    if (live) {
+        int32_t sum = T >= W ? 0 : qsum[i];
+        for (uint32_t s = T - keep; s < T; ++s) {
+            const size_t slot = (size_t)((a.first_step + s) % W) * N + i;
+            const int32_t q = quantise(a.node_z[(size_t)s * N + i], a.quant);
+            if (T < W) sum -= qring[slot];                  // (zero while the window is still filling)
+            sum += q;
+            qring[slot] = (int16_t)q;
+        }
+        qsum[i] = sum;
+    }
+
+    // episode starts, in step order
+    const uint64_t* rise = reinterpret_cast<const uint64_t*>(a.led + a.lay.rise);
+    int32_t* starts = reinterpret_cast<int32_t*>(a.led + a.lay.node_starts);
+    int32_t* term = reinterpret_cast<int32_t*>(a.led + a.lay.node_term);
+    const uint32_t NW = (N + 63) / 64;
+    const uint32_t word = __builtin_amdgcn_readfirstlane(n / 64);
+    int32_t st[MAX_STARTS];
+#pragma unroll
+    for (int j = 0; j < MAX_STARTS; ++j) st[j] = starts[(size_t)j * N + i];
+    int32_t tf = term[i];
+    bool changed = false;
+    for (uint32_t s = 0; s < T; ++s) {
+        const uint64_t w = rise[(size_t)s * NW + word];     // the same word for the whole wave
+        if (w == 0) continue;
+        if (!((w >> lane) & 1ull)) continue;
+        const int64_t t = (int64_t)(a.first_step + s);
+#pragma unroll
+        for (int j = MAX_STARTS - 1; j > 0; --j) st[j] = st[j - 1];
+        st[0] = (int32_t)t + 1;
+        changed = true;
+        // episodes that began inside (t - horizon, t], this one included
+        uint32_t inside = 0;
+#pragma unroll
+        for (int j = 0; j < MAX_STARTS; ++j)
+            inside += (st[j] != 0 && (int64_t)(st[j] - 1) + (int64_t)a.horizon > t) ? 1u : 0u;
+        if (inside >= a.limit && tf == 0) tf = (int32_t)t + 1;
+    }
+    if (live && changed) {
+#pragma unroll
+        for (int j = 0; j < MAX_STARTS; ++j) starts[(size_t)j * N + i] = st[j];
+        term[i] = tf;
+    }
+}
+
+__global__ __launch_bounds__(LED_NT) void ledger_flags_kernel(const gd_ledger_flags_args a) {
+    const uint32_t i = blockIdx.x * LED_NT + threadIdx.x;
+    auto read_out = [&](const uint16_t* cnt, const uint32_t* first, uint32_t n_items, uint8_t* pmask,
+                        uint8_t* pflag, int32_t* pfirst) {
+        uint32_t c[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            c[j] = (uint32_t)cnt[(size_t)(2 * j) * n_items + i] |
+                   ((uint32_t)cnt[(size_t)(2 * j + 1) * n_items + i] << 16);
+        const uint32_t pm = sustained(c, a.K);
+        if (pmask) pmask[i] = (uint8_t)pm;
+        if (pflag) pflag[i] = (uint8_t)combine(pm, a.primary, a.min_signals);
+        if (pfirst) pfirst[i] = first[i] ? (int32_t)(0xFFFFFFFFu - first[i]) : -1;
+    };
+    if (i < a.R)
+        read_out(reinterpret_cast<const uint16_t*>(a.led + a.lay.rank_cnt),
+                 reinterpret_cast<const uint32_t*>(a.led + a.lay.rank_first), a.R, a.rank_pmask,
+                 a.rank_pflag, a.rank_pfirst);
+    if (i < a.N) {
+        read_out(reinterpret_cast<const uint16_t*>(a.led + a.lay.node_cnt),
+                 reinterpret_cast<const uint32_t*>(a.led + a.lay.node_first), a.N, a.node_pmask,
+                 a.node_pflag, a.node_pfirst);
+        if (a.node_score_sum)
+            a.node_score_sum[i] = reinterpret_cast<const int32_t*>(a.led + a.lay.node_qsum)[i];
+        const int32_t* starts = reinterpret_cast<const int32_t*>(a.led + a.lay.node_starts);
+        const uint64_t next = reinterpret_cast<const uint64_t*>(a.led + a.lay.head)[0];
+        if (a.node_episodes) {
+            uint32_t inside = 0;
+            if (next > 0) {
+                const int64_t t = (int64_t)next - 1;        // the last step taken in
+#pragma unroll
+                for (int j = 0; j < MAX_STARTS; ++j) {
+                    const int32_t st = starts[(size_t)j * a.N + i];
+                    inside += (st != 0 && (int64_t)(st - 1) + (int64_t)a.horizon > t) ? 1u : 0u;
+                }
+            }
+            a.node_episodes[i] = (uint8_t)min(inside, a.limit);
+        }
+        if (a.node_terminal_first)
+            a.node_terminal_first[i] = reinterpret_cast<const int32_t*>(a.led + a.lay.node_term)[i] - 1;
+    }
+}
+
+}  // namespace
+
+hipError_t gd_launch_ledger(const gd_ledger_args& a, hipStream_t s) {
+    if (a.T == 0) return hipSuccess;
+    if (a.chunk == 0 || a.limit < 1 || a.limit > (uint32_t)MAX_STARTS) return hipErrorInvalidValue;
+    const uint32_t item_blocks = (a.R + LED_NT - 1) / LED_NT + (a.N + LED_NT - 1) / LED_NT;
+    const uint32_t chunks = (a.T + a.chunk - 1) / a.chunk;
+    if (chunks > 65535u) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(ledger_count_kernel, dim3(item_blocks, chunks), dim3(LED_NT), 0, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const uint32_t node_blocks = (a.N + LED_NT - 1) / LED_NT;
+    const size_t keep = a.T < a.W ? a.T : a.W;
+    const size_t copy_units = keep * (a.R / 4);
+    uint32_t copy_blocks = (uint32_t)((copy_units + LED_NT * 4 - 1) / (LED_NT * 4));
+    copy_blocks = copy_blocks < 1 ? 1 : (copy_blocks > 2048 ? 2048 : copy_blocks);
+    hipLaunchKernelGGL(ledger_finish_kernel, dim3(node_blocks + copy_blocks), dim3(LED_NT), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t gd_launch_ledger_flags(const gd_ledger_flags_args& a, hipStream_t s) {
+    const uint32_t blocks = (a.R + LED_NT - 1) / LED_NT;
+    hipLaunchKernelGGL(ledger_flags_kernel, dim3(blocks), dim3(LED_NT), 0, s, a);
+    return hipGetLastError();
+}

@@ -2,6 +2,10 @@
 // count, latest primary node score, node index) -- the nodes Section 4.2 would
 // remove from the healthy pool first.
 //
+// The middle field of the key is the latest primary node score or, for the
+// ranking by the score averaged over the window, the window's sum of quantised
+// scores.
+//
 // One workgroup builds a unique 64-bit key per node (N <= 8192) and writes the k
 // largest in descending order.
 //
@@ -87,13 +91,15 @@ __global__ __launch_bounds__(TOPK_NT) void topk_kernel(const gd_topk_args a) {
     __shared__ uint64_t keys[TOPK_MAX];
     __shared__ uint64_t threshold;
     __shared__ uint32_t n_reach;
-    const uint16_t* nc = reinterpret_cast<const uint16_t*>(a.state + a.lay.node_count);
-    const float* nz = reinterpret_cast<const float*>(a.state + a.lay.node_z_last);
+    const uint16_t* nc = a.count;
+    const float* nz = a.z_last;
     const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
     auto make_key = [&](uint32_t n) -> uint64_t {
         if (n >= a.N) return 0;                     // padding sorts last
-        const float z = nz[n] + 0.0f;               // -0 ranks as +0
-        return ((uint64_t)nc[n] << 48) | ((uint64_t)key_of(z) << 16) | (uint64_t)(0xFFFFu - n);
+        uint32_t mid;
+        if (nz) mid = key_of(nz[n] + 0.0f);         // -0 ranks as +0
+        else mid = (uint32_t)a.score_sum[n] ^ 0x80000000u;   // sum + 2^31: signed order as unsigned
+        return ((uint64_t)nc[n] << 48) | ((uint64_t)mid << 16) | (uint64_t)(0xFFFFu - n);
     };
     auto write_out = [&](uint32_t i, uint64_t k) {
         a.idx[i] = (int32_t)(0xFFFFu - (uint32_t)(k & 0xFFFFu));

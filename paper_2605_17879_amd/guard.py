@@ -23,7 +23,9 @@ NODE_MAX = 1
 
 EXPORTS = ("gd_default_config", "gd_create", "gd_destroy", "gd_state_bytes", "gd_bind_state",
            "gd_set_streaming_steps", "gd_score_batch", "gd_update_window", "gd_flags",
-           "gd_topk_nodes", "gd_severity", "gd_sweep_score", "gd_probe_read", "gd_last_error")
+           "gd_topk_nodes", "gd_severity", "gd_sweep_score", "gd_probe_read", "gd_last_error",
+           "gd_default_ledger_config", "gd_ledger_bytes", "gd_bind_ledger", "gd_update_ledger",
+           "gd_ledger_flags", "gd_topk_nodes_mean")
 
 
 class GuardError(RuntimeError):
@@ -41,6 +43,12 @@ class _CConfig(ctypes.Structure):
                 ("z_threshold", ctypes.c_float), ("node_scale", ctypes.c_float),
                 ("rel_floor", ctypes.c_float), ("abs_floor", ctypes.c_float),
                 ("direction", ctypes.c_int8 * 8)]
+
+
+class _CLedgerConfig(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("score_quant", ctypes.c_float),
+                ("recur_limit", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
+                ("recur_horizon", ctypes.c_uint64)]
 
 
 def library_path() -> str:
@@ -85,6 +93,18 @@ def load_library() -> ctypes.CDLL:
     lib.gd_sweep_score.restype = ctypes.c_int
     lib.gd_probe_read.argtypes = [vp, vp, u64, vp, vp]
     lib.gd_probe_read.restype = ctypes.c_int
+    lib.gd_default_ledger_config.argtypes = [ctypes.POINTER(_CLedgerConfig)]
+    lib.gd_default_ledger_config.restype = None
+    lib.gd_ledger_bytes.argtypes = [vp, u32]
+    lib.gd_ledger_bytes.restype = ctypes.c_size_t
+    lib.gd_bind_ledger.argtypes = [vp, ctypes.POINTER(_CLedgerConfig), vp, ctypes.c_size_t, u32]
+    lib.gd_bind_ledger.restype = ctypes.c_int
+    lib.gd_update_ledger.argtypes = [vp, vp, vp, vp, u32, u64, vp]
+    lib.gd_update_ledger.restype = ctypes.c_int
+    lib.gd_ledger_flags.argtypes = [vp] * 11
+    lib.gd_ledger_flags.restype = ctypes.c_int
+    lib.gd_topk_nodes_mean.argtypes = [vp, u32, vp, vp, vp]
+    lib.gd_topk_nodes_mean.restype = ctypes.c_int
     lib.gd_last_error.argtypes = [vp]
     lib.gd_last_error.restype = ctypes.c_char_p
     _lib = lib
@@ -270,3 +290,54 @@ class Detector:
     def topk_nodes(self, k: int, tk: dict, stream=None):
         self._check(self.lib.gd_topk_nodes(self.h, k, _p(tk["idx"]), _p(tk.get("key")),
                                            self._stream(stream)))
+
+    # ---- the ledger ---------------------------------------------------------------
+    def ledger_bytes(self, max_T: int) -> int:
+        return int(self.lib.gd_ledger_bytes(self.h, max_T))
+
+    def bind_ledger(self, ledger, max_T: int, score_quant: Optional[float] = None,
+                    recur_limit: Optional[int] = None, recur_horizon: Optional[int] = None):
+        c = _CLedgerConfig()
+        self.lib.gd_default_ledger_config(ctypes.byref(c))
+        if score_quant is not None:
+            c.score_quant = score_quant
+        if recur_limit is not None:
+            c.recur_limit = recur_limit
+        if recur_horizon is not None:
+            c.recur_horizon = recur_horizon
+        self._check(self.lib.gd_bind_ledger(self.h, ctypes.byref(c), ledger.data_ptr(),
+                                            ledger.numel() * ledger.element_size(), max_T))
+        self.ledger = ledger
+        self.ledger_steps_seen = 0
+
+    def alloc_ledger(self, max_T: int, **cfg):
+        """A fresh (zeroed) ledger for batches of up to max_T steps, bound to the handle."""
+        led = self._torch.zeros(self.ledger_bytes(max_T), dtype=self._torch.uint8, device=self.device)
+        self.bind_ledger(led, max_T, **cfg)
+        return led
+
+    def update_ledger(self, out: dict, T: int, first_step_index: Optional[int] = None, stream=None):
+        first = self.ledger_steps_seen if first_step_index is None else first_step_index
+        self._check(self.lib.gd_update_ledger(self.h, _p(out["exceed_mask"]), _p(out["node_mask"]),
+                                              _p(out["node_z"]), T, first, self._stream(stream)))
+        self.ledger_steps_seen = first + T
+
+    def alloc_ledger_flags(self) -> dict:
+        torch, d = self._torch, self.device
+        e = lambda n, t: torch.empty(n, dtype=t, device=d)
+        return dict(rank_pmask=e(self.R, torch.uint8), rank_pflag=e(self.R, torch.uint8),
+                    rank_pfirst=e(self.R, torch.int32), node_pmask=e(self.N, torch.uint8),
+                    node_pflag=e(self.N, torch.uint8), node_pfirst=e(self.N, torch.int32),
+                    node_score_sum=e(self.N, torch.int32), node_episodes=e(self.N, torch.uint8),
+                    node_terminal_first=e(self.N, torch.int32))
+
+    def ledger_flags(self, f: dict, stream=None):
+        self._check(self.lib.gd_ledger_flags(
+            self.h, _p(f.get("rank_pmask")), _p(f.get("rank_pflag")), _p(f.get("rank_pfirst")),
+            _p(f.get("node_pmask")), _p(f.get("node_pflag")), _p(f.get("node_pfirst")),
+            _p(f.get("node_score_sum")), _p(f.get("node_episodes")),
+            _p(f.get("node_terminal_first")), self._stream(stream)))
+
+    def topk_nodes_mean(self, k: int, tk: dict, stream=None):
+        self._check(self.lib.gd_topk_nodes_mean(self.h, k, _p(tk["idx"]), _p(tk.get("key")),
+                                                self._stream(stream)))

@@ -82,6 +82,48 @@ def test_state_size_and_argument_checks_without_a_device():
     assert lib.gd_destroy(h) == 0
 
 
+def test_ledger_size_and_argument_checks_without_a_device():
+    lib, st, h = make(R=1024, M=4, W=50, k=40)
+    assert st == 0
+    c = guard._CLedgerConfig()
+    lib.gd_default_ledger_config(ctypes.byref(c))
+    assert c.struct_size == ctypes.sizeof(guard._CLedgerConfig) == 24
+    assert (c.score_quant, c.recur_limit, c.recur_horizon) == (64.0, 3, 604800)
+    up = lambda b: (b + 255) // 256 * 256
+    counts = up(1024 * 16) + up(128 * 16) + up(128 * 2)
+    want = (up(32) + up(50 * 1024) + up(50 * 128) + 2 * counts + up(1024 * 4) + up(128 * 4) +
+            up(50 * 128 * 2) + up(128 * 4) + up(128 * 32) + up(128 * 4) + up(300 * 2 * 8))
+    n = lib.gd_ledger_bytes(h, 300)
+    assert n == want
+    assert lib.gd_ledger_bytes(None, 300) == 0
+    # nothing bound yet
+    assert lib.gd_update_ledger(h, 256, 256, 256, 1, 0, None) == 1
+    assert lib.gd_ledger_flags(h, *([None] * 10)) == 1
+    assert lib.gd_topk_nodes_mean(h, 4, 256, None, None) == 1
+    # binding: null, misaligned, too small, bad configurations
+    assert lib.gd_bind_ledger(h, ctypes.byref(c), None, n, 300) == 1
+    assert lib.gd_bind_ledger(h, None, 4096, n, 300) == 1
+    assert lib.gd_bind_ledger(h, ctypes.byref(c), 4096 + 8, n, 300) == 1
+    assert lib.gd_bind_ledger(h, ctypes.byref(c), 4096, n - 1, 300) == 3
+    assert lib.gd_bind_ledger(h, ctypes.byref(c), 4096, n, 0) == 1
+    for name, bad in (("score_quant", 0.0), ("score_quant", float("inf")), ("recur_limit", 0),
+                      ("recur_limit", 9), ("recur_horizon", 0), ("struct_size", 8)):
+        d = guard._CLedgerConfig()
+        lib.gd_default_ledger_config(ctypes.byref(d))
+        setattr(d, name, bad)
+        assert lib.gd_bind_ledger(h, ctypes.byref(d), 4096, n, 300) == 2, name
+    # bound (the address is never touched without a launch): argument checks of the update
+    assert lib.gd_bind_ledger(h, ctypes.byref(c), 4096, n, 300) == 0
+    assert lib.gd_update_ledger(h, None, None, None, 0, 0, None) == 0          # T == 0: no-op
+    assert lib.gd_update_ledger(h, None, 256, 256, 1, 0, None) == 1
+    assert lib.gd_update_ledger(h, 256, 256, 256, 301, 0, None) == 1           # more than max_T
+    assert lib.gd_update_ledger(h, 256 + 1, 256, 256, 1, 0, None) == 1         # misaligned
+    assert lib.gd_update_ledger(h, 256, 256, 256, 2, 2**31 - 2, None) == 1     # step index too large
+    assert lib.gd_topk_nodes_mean(h, 129, 256, None, None) == 1
+    assert lib.gd_topk_nodes_mean(h, 4, None, None, None) == 1
+    assert lib.gd_destroy(h) == 0
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(guard, "_lib", None)
     monkeypatch.setattr(guard, "_LIB_PATH", str(tmp_path / "missing.so"))
