@@ -126,6 +126,28 @@ def detection_report(torch, det, w, x, out, fl) -> dict:
                                         "moderate": tiers[2], "severe": tiers[3]}}
 
 
+def ledger_leg(torch, det, w, out, stream) -> dict:
+    """The bookkeeping beyond the default rule on the same resident scoring outputs
+    (persistence per indicator, windowed score sums and their ranking, recurrence):
+    not part of `value`, timed on its own."""
+    det.alloc_ledger(w.T)
+    lf, tk = det.alloc_ledger_flags(), det.alloc_topk(w.topk)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
+    with torch.cuda.stream(stream):
+        for s0, s1 in ev:
+            s0.record(stream)
+            det.update_ledger(out, w.T, stream=stream)
+            det.ledger_flags(lf, stream)
+            det.topk_nodes_mean(w.topk, tk, stream)
+            s1.record(stream)
+        torch.cuda.synchronize()
+    ms = sorted(s0.elapsed_time(s1) for s0, s1 in ev)[2]
+    N = w.R // w.G
+    read = w.T * (w.R + N) + min(w.T, w.W) * N * 4          # exceed bytes of ranks and nodes, the window's node scores
+    return {"what": "update_ledger + ledger_flags + topk_nodes_mean on the batch's scoring outputs",
+            "ms": ms, "input_bytes": read, "GB/s": read / (ms * 1e-3) / 1e9}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -212,6 +234,7 @@ def main() -> int:
                                            "what": "the same loads with no arithmetic (gd_probe_read)"}},
     }
     res["detection"] = detection_report(torch, det, w, x, out, fl)
+    res["ledger"] = ledger_leg(torch, det, w, out, stream)
     if not a.no_cpu:
         res["cpu_baseline"] = cpu_baseline(w, x, a.cpu_sample_steps)
     del x, out

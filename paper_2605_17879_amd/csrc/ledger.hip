@@ -11,10 +11,12 @@
 //  * Recurrence: how many flag episodes of a node began within a horizon (a node
 //    sent to triage three times within a week is terminally bad, Section 7).
 //
-// ledger_count_kernel: one thread per item (a rank or a node) and per chunk of
-// steps.  The per-metric counts live in four registers as eight 16-bit fields; a
-// step whose entering and leaving exceed bytes are equal (nearly all are) costs
-// two byte loads and a compare.  A chunk other than the first rebuilds its
+// ledger_count_kernel: one thread per item (a node, or four ranks) and per chunk
+// of steps.  The per-metric counts live in four registers as eight 16-bit fields,
+// biased so that a field's top bit says "reached k"; a step adds the entering
+// byte's bits and takes off the leaving byte's through a 256-entry table in LDS
+// (byte -> eight fields), and the rule itself is evaluated only while the primary
+// metric's top bit is on and no flagged step has been found yet.  A chunk other than the first rebuilds its
 // starting counts from the W steps before it, so chunks are independent; the
 // first flagged step is the minimum over chunks (an atomic max on 0xFFFFFFFF -
 // step).  For nodes the kernel also follows the default rule's own flag and
@@ -55,14 +57,33 @@ __device__ __forceinline__ uint32_t combine(uint32_t bits, uint32_t primary, uin
     return ((bits >> primary) & 1u) && (uint32_t)__popc(bits) >= min_signals ? 1u : 0u;
 }
 
-template <bool NODE>
-__device__ __forceinline__ void count_items(const gd_ledger_args& a, uint32_t blk) {
-    const uint32_t n_items = NODE ? a.N : a.R;
-    const uint32_t item = blk * LED_NT + threadIdx.x;
+// The rule on biased counts (each 16-bit field holds count + 0x8000 - K, so its top
+// bit says "sustained"): primary sustained and at least min_signals fields are.
+__device__ __forceinline__ uint32_t rule_on_biased(const uint32_t (&c)[4], uint32_t primary,
+                                                   uint32_t min_signals) {
+    uint32_t n = 0, prim = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t top = c[j] & 0x80008000u;
+        n += (uint32_t)__popc(top);
+        if ((primary >> 1) == (uint32_t)j) prim = top >> (15 + 16 * (primary & 1u));
+    }
+    return (prim & 1u) && n >= min_signals ? 1u : 0u;
+}
+
+// IPT items per thread: ranks go four at a time (one 4-byte load per step), nodes
+// singly, so that a wave's ballot is one word of the episode-start map.
+// spread[b] (LDS, 256 entries) = the eight bits of byte b as eight 16-bit fields.
+template <bool NODE, int IPT>
+__device__ __forceinline__ void count_items(const gd_ledger_args& a, uint32_t blk, const uint4* spread) {
+    static_assert(IPT == 1 || IPT == 4, "count_items");
+    static_assert(!NODE || IPT == 1, "count_items");
+    const uint32_t n_items = NODE ? a.N : a.R;              // (R is a multiple of 8)
+    const uint32_t item = (blk * LED_NT + threadIdx.x) * IPT;
     const uint32_t lane = threadIdx.x & (WAVE - 1);
-    if (item - lane >= n_items) return;                     // whole wave out of range
+    if (item - lane * IPT >= n_items) return;               // whole wave out of range
     const bool live = item < n_items;
-    const uint32_t i = live ? item : n_items - 1;           // idle lanes repeat the last item, store nothing
+    const uint32_t i = live ? item : n_items - IPT;         // idle lanes repeat the last items, store nothing
     const uint8_t* mask = NODE ? a.node_mask : a.exceed_mask;
     const uint8_t* ring = a.led + (NODE ? a.lay.node_ring : a.lay.rank_ring);
     uint16_t* cnt = reinterpret_cast<uint16_t*>(a.led + (NODE ? a.lay.node_cnt : a.lay.rank_cnt));
@@ -70,36 +91,60 @@ __device__ __forceinline__ void count_items(const gd_ledger_args& a, uint32_t bl
     uint16_t* ccnt = reinterpret_cast<uint16_t*>(a.led + a.lay.node_ccnt);
     uint64_t* rise = reinterpret_cast<uint64_t*>(a.led + a.lay.rise);
     const uint32_t W = a.W, K = a.K, T = a.T;
-    const uint32_t NW = (a.N + 63) / 64;
     const uint32_t s0 = blockIdx.y * a.chunk;
     const uint32_t s1 = min(T, s0 + a.chunk);
     if (s0 >= s1) return;
+    const uint32_t bias = (0x8000u - K) * 0x00010001u;      // counts <= 1024 and 1 <= K <= 1024: fields never wrap
 
-    // the exceed byte of step s of the batch; s < 0 reaches back into the ring
-    auto hist = [&](int64_t s) -> uint32_t {
-        if (s >= 0) return mask[(size_t)s * n_items + i];
-        const int64_t g = (int64_t)a.first_step + s;
-        return g >= 0 ? ring[(size_t)(g % W) * n_items + i] : 0u;
+    auto load = [&](const uint8_t* row) -> uint32_t {       // the IPT exceed bytes of this thread
+        if (IPT == 4) return *reinterpret_cast<const uint32_t*>(row + i);
+        return row[i];
     };
+    // the exceed bytes of step s of the batch; s < 0 reaches back into the ring
+    auto hist = [&](int64_t s) -> uint32_t {
+        if (s >= 0) return load(mask + (size_t)s * n_items);
+        const int64_t g = (int64_t)a.first_step + s;
+        return g >= 0 ? load(ring + (size_t)(g % W) * n_items) : 0u;
+    };
+    auto add_fields = [&](uint32_t (&c)[4], const uint4 v) { c[0] += v.x; c[1] += v.y; c[2] += v.z; c[3] += v.w; };
 
-    uint32_t c[4] = {0, 0, 0, 0};
+    uint32_t c[IPT][4];                                     // biased counts
     uint32_t cc = 0;                                        // the default rule's count (nodes)
     if (s0 == 0) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            c[j] = (uint32_t)cnt[(size_t)(2 * j) * n_items + i] |
-                   ((uint32_t)cnt[(size_t)(2 * j + 1) * n_items + i] << 16);
+        for (int k = 0; k < IPT; ++k)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                c[k][j] = ((uint32_t)cnt[(size_t)(2 * j) * n_items + i + k] |
+                           ((uint32_t)cnt[(size_t)(2 * j + 1) * n_items + i + k] << 16)) + bias;
         if (NODE) cc = ccnt[i];
     } else {
-        for (int64_t s = (int64_t)s0 - W; s < (int64_t)s0; ++s) {
-            const uint32_t b = hist(s);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) c[j] += spread2(b, j);
-            if (NODE) cc += combine(b, a.primary, a.min_signals);
+        for (int k = 0; k < IPT; ++k)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) c[k][j] = bias;
+        for (int64_t s = (int64_t)s0 - W; s < (int64_t)s0; s += LED_AHEAD) {
+            uint32_t hb[LED_AHEAD];
+#pragma unroll
+            for (int q = 0; q < LED_AHEAD; ++q) hb[q] = s + q < (int64_t)s0 ? hist(s + q) : 0u;
+#pragma unroll
+            for (int q = 0; q < LED_AHEAD; ++q) {
+#pragma unroll
+                for (int k = 0; k < IPT; ++k) {
+                    const uint32_t b = (hb[q] >> (8 * k)) & 0xFFu;
+                    add_fields(c[k], spread[b]);
+                    if (NODE) cc += combine(b, a.primary, a.min_signals);
+                }
+            }
         }
     }
-    uint32_t pflag = combine(sustained(c, K), a.primary, a.min_signals);
-    uint32_t best = 0;                                      // 0xFFFFFFFF - first flagged step of the chunk
+    // the primary metric's top bit, as one mask per count word (three of them zero)
+    uint32_t pmask[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) pmask[j] = (a.primary >> 1) == (uint32_t)j ? 0x8000u << (16 * (a.primary & 1u)) : 0u;
+    uint32_t best[IPT];                                     // 0xFFFFFFFF - first flagged step of the chunk
+#pragma unroll
+    for (int k = 0; k < IPT; ++k) best[k] = 0;
     bool cflag = NODE && cc >= K;                           // the default rule's flag one step earlier
 
     for (uint32_t s = s0; s < s1; s += LED_AHEAD) {
@@ -108,49 +153,69 @@ __device__ __forceinline__ void count_items(const gd_ledger_args& a, uint32_t bl
         for (int q = 0; q < LED_AHEAD; ++q) {
             eb[q] = 0; lb[q] = 0;
             if (s + q < s1) {
-                eb[q] = mask[(size_t)(s + q) * n_items + i];
+                eb[q] = load(mask + (size_t)(s + q) * n_items);
                 lb[q] = hist((int64_t)(s + q) - W);
             }
         }
 #pragma unroll
         for (int q = 0; q < LED_AHEAD; ++q) {
             if (s + q >= s1) break;                         // uniform over the wave
-            const uint32_t e = eb[q], l = lb[q];
-            if (e != l) {
+            const uint32_t step_code = 0xFFFFFFFFu - (uint32_t)(a.first_step + s + q);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) c[j] = c[j] + spread2(e, j) - spread2(l, j);
-                pflag = combine(sustained(c, K), a.primary, a.min_signals);
+            for (int k = 0; k < IPT; ++k) {
+                const uint32_t e = (eb[q] >> (8 * k)) & 0xFFu, l = (lb[q] >> (8 * k)) & 0xFFu;
+                const uint4 se = spread[e], sl = spread[l];
+                c[k][0] += se.x - sl.x; c[k][1] += se.y - sl.y;
+                c[k][2] += se.z - sl.z; c[k][3] += se.w - sl.w;
+                // the rule needs the primary metric sustained, which it rarely is: only then look further
+                const uint32_t prim_up = (c[k][0] & pmask[0]) | (c[k][1] & pmask[1]) | (c[k][2] & pmask[2]) |
+                                         (c[k][3] & pmask[3]);
+                if (prim_up && !best[k] && rule_on_biased(c[k], a.primary, a.min_signals))
+                    best[k] = step_code;
                 if (NODE) cc = cc + combine(e, a.primary, a.min_signals) - combine(l, a.primary, a.min_signals);
             }
-            if (pflag && !best) best = 0xFFFFFFFFu - (uint32_t)(a.first_step + s + q);
             if (NODE) {
                 const bool now = cc >= K;
                 const uint64_t rb = __ballot(live && now && !cflag);
                 cflag = now;
-                if (lane == 0) rise[(size_t)(s + q) * NW + item / 64] = rb;
+                // one word per (64 nodes, step), the steps of a word side by side
+                if (lane == 0) rise[(size_t)(item / 64) * T + (s + q)] = rb;
             }
         }
     }
     if (!live) return;
-    if (best) atomicMax(&first[i], best);
+#pragma unroll
+    for (int k = 0; k < IPT; ++k)
+        if (best[k]) atomicMax(&first[i + k], best[k]);
     if (s1 == T) {
         // With several chunks the first one may still have to read the old counts:
         // the new ones go to the staging span and the finishing kernel moves them.
         const size_t shift = gridDim.y > 1 ? (a.lay.counts_new - a.lay.rank_cnt) / 2 : 0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            cnt[shift + (size_t)(2 * j) * n_items + i] = (uint16_t)(c[j] & 0xFFFFu);
-            cnt[shift + (size_t)(2 * j + 1) * n_items + i] = (uint16_t)(c[j] >> 16);
-        }
+        for (int k = 0; k < IPT; ++k)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t v = c[k][j] - bias;
+                cnt[shift + (size_t)(2 * j) * n_items + i + k] = (uint16_t)(v & 0xFFFFu);
+                cnt[shift + (size_t)(2 * j + 1) * n_items + i + k] = (uint16_t)(v >> 16);
+            }
         if (NODE) ccnt[shift + i] = (uint16_t)cc;
     }
 }
 
+constexpr int RANK_IPT = 4;
+
 // Blocks [0, rank_blocks) take ranks, the rest nodes; blockIdx.y is the chunk.
 __global__ __launch_bounds__(LED_NT) void ledger_count_kernel(const gd_ledger_args a) {
-    const uint32_t rank_blocks = (a.R + LED_NT - 1) / LED_NT;
-    if (blockIdx.x < rank_blocks) count_items<false>(a, blockIdx.x);
-    else count_items<true>(a, blockIdx.x - rank_blocks);
+    __shared__ uint4 spread[256];
+    {
+        const uint32_t b = threadIdx.x;                     // LED_NT == 256: one entry per thread
+        spread[b] = make_uint4(spread2(b, 0), spread2(b, 1), spread2(b, 2), spread2(b, 3));
+    }
+    __syncthreads();
+    const uint32_t rank_blocks = (a.R / RANK_IPT + LED_NT - 1) / LED_NT;
+    if (blockIdx.x < rank_blocks) count_items<false, RANK_IPT>(a, blockIdx.x, spread);
+    else count_items<true, 1>(a, blockIdx.x - rank_blocks, spread);
 }
 
 __device__ __forceinline__ int32_t quantise(float z, float quant) {
@@ -205,42 +270,71 @@ __global__ __launch_bounds__(LED_NT) void ledger_finish_kernel(const gd_ledger_a
     int32_t* qsum = reinterpret_cast<int32_t*>(a.led + a.lay.node_qsum);
     if (live) {
         int32_t sum = T >= W ? 0 : qsum[i];
-        for (uint32_t s = T - keep; s < T; ++s) {
-            const size_t slot = (size_t)((a.first_step + s) % W) * N + i;
-            const int32_t q = quantise(a.node_z[(size_t)s * N + i], a.quant);
-            if (T < W) sum -= qring[slot];                  // (zero while the window is still filling)
-            sum += q;
-            qring[slot] = (int16_t)q;
+        for (uint32_t s = T - keep; s < T; s += LED_AHEAD) {
+            float z[LED_AHEAD];
+            int32_t old[LED_AHEAD];
+#pragma unroll
+            for (int q = 0; q < LED_AHEAD; ++q) {
+                z[q] = 0.0f; old[q] = 0;
+                if (s + q < T) {
+                    z[q] = a.node_z[(size_t)(s + q) * N + i];
+                    // (zero while the window is still filling; a batch of W steps or more starts afresh)
+                    if (T < W) old[q] = qring[(size_t)((a.first_step + s + q) % W) * N + i];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < LED_AHEAD; ++q) {
+                if (s + q >= T) break;
+                const int32_t v = quantise(z[q], a.quant);
+                sum += v - old[q];
+                qring[(size_t)((a.first_step + s + q) % W) * N + i] = (int16_t)v;
+            }
         }
         qsum[i] = sum;
     }
 
-    // episode starts, in step order
+    // episode starts, in step order: lane l fetches the word of step s + l, and the few
+    // words that hold a start are handed round
     const uint64_t* rise = reinterpret_cast<const uint64_t*>(a.led + a.lay.rise);
     int32_t* starts = reinterpret_cast<int32_t*>(a.led + a.lay.node_starts);
     int32_t* term = reinterpret_cast<int32_t*>(a.led + a.lay.node_term);
-    const uint32_t NW = (N + 63) / 64;
     const uint32_t word = __builtin_amdgcn_readfirstlane(n / 64);
     int32_t st[MAX_STARTS];
 #pragma unroll
     for (int j = 0; j < MAX_STARTS; ++j) st[j] = starts[(size_t)j * N + i];
     int32_t tf = term[i];
     bool changed = false;
-    for (uint32_t s = 0; s < T; ++s) {
-        const uint64_t w = rise[(size_t)s * NW + word];     // the same word for the whole wave
-        if (w == 0) continue;
-        if (!((w >> lane) & 1ull)) continue;
-        const int64_t t = (int64_t)(a.first_step + s);
+    constexpr int BLOCKS = 4;                               // 64-step words fetched together
+    for (uint32_t s = 0; s < T; s += BLOCKS * WAVE) {
+        uint64_t v[BLOCKS];
 #pragma unroll
-        for (int j = MAX_STARTS - 1; j > 0; --j) st[j] = st[j - 1];
-        st[0] = (int32_t)t + 1;
-        changed = true;
-        // episodes that began inside (t - horizon, t], this one included
-        uint32_t inside = 0;
+        for (int q = 0; q < BLOCKS; ++q) {
+            const uint32_t sq = s + q * WAVE + lane;
+            v[q] = sq < T ? rise[(size_t)word * T + sq] : 0ull;
+        }
 #pragma unroll
-        for (int j = 0; j < MAX_STARTS; ++j)
-            inside += (st[j] != 0 && (int64_t)(st[j] - 1) + (int64_t)a.horizon > t) ? 1u : 0u;
-        if (inside >= a.limit && tf == 0) tf = (int32_t)t + 1;
+        for (int q = 0; q < BLOCKS; ++q) {
+            uint64_t any = __ballot(v[q] != 0);
+            while (any) {
+                const int j = __builtin_ctzll(any);
+                any &= any - 1;
+                const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v[q], j);
+                const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v[q] >> 32), j);
+                const uint64_t w = ((uint64_t)hi << 32) | lo;
+                if (!((w >> lane) & 1ull)) continue;
+                const int64_t t = (int64_t)(a.first_step + s + q * WAVE + j);
+#pragma unroll
+                for (int jj = MAX_STARTS - 1; jj > 0; --jj) st[jj] = st[jj - 1];
+                st[0] = (int32_t)t + 1;
+                changed = true;
+                // episodes that began inside (t - horizon, t], this one included
+                uint32_t inside = 0;
+#pragma unroll
+                for (int jj = 0; jj < MAX_STARTS; ++jj)
+                    inside += (st[jj] != 0 && (int64_t)(st[jj] - 1) + (int64_t)a.horizon > t) ? 1u : 0u;
+                if (inside >= a.limit && tf == 0) tf = (int32_t)t + 1;
+            }
+        }
     }
     if (live && changed) {
 #pragma unroll
@@ -297,7 +391,7 @@ __global__ __launch_bounds__(LED_NT) void ledger_flags_kernel(const gd_ledger_fl
 hipError_t gd_launch_ledger(const gd_ledger_args& a, hipStream_t s) {
     if (a.T == 0) return hipSuccess;
     if (a.chunk == 0 || a.limit < 1 || a.limit > (uint32_t)MAX_STARTS) return hipErrorInvalidValue;
-    const uint32_t item_blocks = (a.R + LED_NT - 1) / LED_NT + (a.N + LED_NT - 1) / LED_NT;
+    const uint32_t item_blocks = (a.R / RANK_IPT + LED_NT - 1) / LED_NT + (a.N + LED_NT - 1) / LED_NT;
     const uint32_t chunks = (a.T + a.chunk - 1) / a.chunk;
     if (chunks > 65535u) return hipErrorInvalidValue;
     hipLaunchKernelGGL(ledger_count_kernel, dim3(item_blocks, chunks), dim3(LED_NT), 0, s, a);
