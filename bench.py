@@ -50,6 +50,21 @@ def measured_traffic():
     return None
 
 
+VALU_PER_SAMPLE = 28.9      # SQ_INSTS_VALU x 64 / samples, profiles/score_kernel_c3_counters.txt
+SIMDS, CLOCK_HZ = 1024, 2.4e9
+
+
+def issue_view(samples: int, score_ms: float) -> dict:
+    """Why the HBM fraction is what it is: the share of all SIMD cycles of the chip
+    (256 CUs x 4 SIMDs at 2.4 GHz, one 64-lane vector instruction per 4 cycles) that the
+    scoring launch spends issuing vector instructions, from the profiled instruction
+    count per sample and this run's launch time."""
+    cycles = VALU_PER_SAMPLE * samples / 64 * 4
+    return {"valu_instructions_per_sample": VALU_PER_SAMPLE,
+            "simd_cycles_issuing_valu": cycles / (score_ms * 1e-3 * CLOCK_HZ * SIMDS),
+            "what": "instruction count from rocprofv3 counters (profiles/), time from this run"}
+
+
 def make_detector(w):
     from paper_2605_17879_amd import Config, Detector
     return Detector(Config(n_ranks=w.R, n_metrics=w.M, window=w.W, persist_k=w.k,
@@ -231,7 +246,8 @@ def main() -> int:
                      "traffic": measured_traffic(), "algorithmic_bytes": alg,
                      "avg_launch_ms": score_ms,
                      "read_only_ceiling": {"GB/s": x.numel() * 4 / (read_ms * 1e-3) / 1e9, "ms": read_ms,
-                                           "what": "the same loads with no arithmetic (gd_probe_read)"}},
+                                           "what": "the same loads with no arithmetic (gd_probe_read)"},
+                     "issue_view": issue_view(w.samples, score_ms)},
     }
     res["detection"] = detection_report(torch, det, w, x, out, fl)
     res["ledger"] = ledger_leg(torch, det, w, out, stream)

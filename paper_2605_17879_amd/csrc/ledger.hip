@@ -58,22 +58,25 @@ __device__ __forceinline__ uint32_t combine(uint32_t bits, uint32_t primary, uin
 }
 
 // The rule on biased counts (each 16-bit field holds count + 0x8000 - K, so its top
-// bit says "sustained"): primary sustained and at least min_signals fields are.
-__device__ __forceinline__ uint32_t rule_on_biased(const uint32_t (&c)[4], uint32_t primary,
-                                                   uint32_t min_signals) {
-    uint32_t n = 0, prim = 0;
+// bit says "sustained"; the primary metric's field is the low half of word 0):
+// primary sustained and at least min_signals fields are.
+__device__ __forceinline__ uint32_t rule_on_biased(const uint32_t (&c)[4], uint32_t min_signals) {
+    uint32_t n = 0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const uint32_t top = c[j] & 0x80008000u;
-        n += (uint32_t)__popc(top);
-        if ((primary >> 1) == (uint32_t)j) prim = top >> (15 + 16 * (primary & 1u));
-    }
-    return (prim & 1u) && n >= min_signals ? 1u : 0u;
+    for (int j = 0; j < 4; ++j) n += (uint32_t)__popc(c[j] & 0x80008000u);
+    return (c[0] & 0x8000u) && n >= min_signals ? 1u : 0u;
+}
+
+// Field f of the count words belongs to metric field_metric(f): the identity but for
+// the primary metric and metric 0, which change places.
+__device__ __forceinline__ uint32_t field_metric(uint32_t f, uint32_t primary) {
+    return f == 0 ? primary : (f == primary ? 0u : f);
 }
 
 // IPT items per thread: ranks go four at a time (one 4-byte load per step), nodes
 // singly, so that a wave's ballot is one word of the episode-start map.
-// spread[b] (LDS, 256 entries) = the eight bits of byte b as eight 16-bit fields.
+// spread[b] (LDS) = the eight bits of byte b as eight 16-bit fields, spread[256 + b]
+// the same words negated, so that one three-operand add per word takes a step.
 template <bool NODE, int IPT>
 __device__ __forceinline__ void count_items(const gd_ledger_args& a, uint32_t blk, const uint4* spread) {
     static_assert(IPT == 1 || IPT == 4, "count_items");
@@ -115,8 +118,8 @@ __device__ __forceinline__ void count_items(const gd_ledger_args& a, uint32_t bl
         for (int k = 0; k < IPT; ++k)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                c[k][j] = ((uint32_t)cnt[(size_t)(2 * j) * n_items + i + k] |
-                           ((uint32_t)cnt[(size_t)(2 * j + 1) * n_items + i + k] << 16)) + bias;
+                c[k][j] = ((uint32_t)cnt[(size_t)field_metric(2 * j, a.primary) * n_items + i + k] |
+                           ((uint32_t)cnt[(size_t)field_metric(2 * j + 1, a.primary) * n_items + i + k] << 16)) + bias;
         if (NODE) cc = ccnt[i];
     } else {
 #pragma unroll
@@ -138,10 +141,6 @@ __device__ __forceinline__ void count_items(const gd_ledger_args& a, uint32_t bl
             }
         }
     }
-    // the primary metric's top bit, as one mask per count word (three of them zero)
-    uint32_t pmask[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) pmask[j] = (a.primary >> 1) == (uint32_t)j ? 0x8000u << (16 * (a.primary & 1u)) : 0u;
     uint32_t best[IPT];                                     // 0xFFFFFFFF - first flagged step of the chunk
 #pragma unroll
     for (int k = 0; k < IPT; ++k) best[k] = 0;
@@ -164,14 +163,11 @@ __device__ __forceinline__ void count_items(const gd_ledger_args& a, uint32_t bl
 #pragma unroll
             for (int k = 0; k < IPT; ++k) {
                 const uint32_t e = (eb[q] >> (8 * k)) & 0xFFu, l = (lb[q] >> (8 * k)) & 0xFFu;
-                const uint4 se = spread[e], sl = spread[l];
-                c[k][0] += se.x - sl.x; c[k][1] += se.y - sl.y;
-                c[k][2] += se.z - sl.z; c[k][3] += se.w - sl.w;
+                const uint4 se = spread[e], nl = spread[256 + l];
+                c[k][0] += se.x + nl.x; c[k][1] += se.y + nl.y;
+                c[k][2] += se.z + nl.z; c[k][3] += se.w + nl.w;
                 // the rule needs the primary metric sustained, which it rarely is: only then look further
-                const uint32_t prim_up = (c[k][0] & pmask[0]) | (c[k][1] & pmask[1]) | (c[k][2] & pmask[2]) |
-                                         (c[k][3] & pmask[3]);
-                if (prim_up && !best[k] && rule_on_biased(c[k], a.primary, a.min_signals))
-                    best[k] = step_code;
+                if ((c[k][0] & 0x8000u) && !best[k] && rule_on_biased(c[k], a.min_signals)) best[k] = step_code;
                 if (NODE) cc = cc + combine(e, a.primary, a.min_signals) - combine(l, a.primary, a.min_signals);
             }
             if (NODE) {
@@ -196,8 +192,8 @@ __device__ __forceinline__ void count_items(const gd_ledger_args& a, uint32_t bl
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const uint32_t v = c[k][j] - bias;
-                cnt[shift + (size_t)(2 * j) * n_items + i + k] = (uint16_t)(v & 0xFFFFu);
-                cnt[shift + (size_t)(2 * j + 1) * n_items + i + k] = (uint16_t)(v >> 16);
+                cnt[shift + (size_t)field_metric(2 * j, a.primary) * n_items + i + k] = (uint16_t)(v & 0xFFFFu);
+                cnt[shift + (size_t)field_metric(2 * j + 1, a.primary) * n_items + i + k] = (uint16_t)(v >> 16);
             }
         if (NODE) ccnt[shift + i] = (uint16_t)cc;
     }
@@ -207,10 +203,15 @@ constexpr int RANK_IPT = 4;
 
 // Blocks [0, rank_blocks) take ranks, the rest nodes; blockIdx.y is the chunk.
 __global__ __launch_bounds__(LED_NT) void ledger_count_kernel(const gd_ledger_args a) {
-    __shared__ uint4 spread[256];
+    __shared__ uint4 spread[512];
     {
-        const uint32_t b = threadIdx.x;                     // LED_NT == 256: one entry per thread
-        spread[b] = make_uint4(spread2(b, 0), spread2(b, 1), spread2(b, 2), spread2(b, 3));
+        const uint32_t b = threadIdx.x;                     // LED_NT == 256: one byte value per thread
+        // bit 0 and the primary metric's bit change places: its field is the low half of word 0
+        const uint32_t b0 = b & 1u, bp = (b >> a.primary) & 1u;
+        const uint32_t v = (b & ~(1u | (1u << a.primary))) | bp | (b0 << a.primary);
+        const uint4 f = make_uint4(spread2(v, 0), spread2(v, 1), spread2(v, 2), spread2(v, 3));
+        spread[b] = f;
+        spread[256 + b] = make_uint4(0u - f.x, 0u - f.y, 0u - f.z, 0u - f.w);
     }
     __syncthreads();
     const uint32_t rank_blocks = (a.R / RANK_IPT + LED_NT - 1) / LED_NT;
