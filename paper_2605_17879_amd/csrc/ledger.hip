@@ -106,8 +106,8 @@ __device__ __forceinline__ void count_items(const gd_ledger_args& a, uint32_t bl
     // the exceed bytes of step s of the batch; s < 0 reaches back into the ring
     auto hist = [&](int64_t s) -> uint32_t {
         if (s >= 0) return load(mask + (size_t)s * n_items);
-        const int64_t g = (int64_t)a.first_step + s;
-        return g >= 0 ? load(ring + (size_t)(g % W) * n_items) : 0u;
+        const int64_t g = (int64_t)a.first_step + s;        // (below 2^31)
+        return g >= 0 ? load(ring + (size_t)((uint32_t)g % W) * n_items) : 0u;
     };
     auto add_fields = [&](uint32_t (&c)[4], const uint4 v) { c[0] += v.x; c[1] += v.y; c[2] += v.z; c[3] += v.w; };
 
