@@ -82,6 +82,8 @@ def _load():
                                      ctypes.c_float, ctypes.c_float, vp, vp]
         _lib.go_severity.restype = None
         u32, u64 = ctypes.c_uint32, ctypes.c_uint64
+        _lib.go_combine.argtypes = [u32, u32, u32, vp, u64, vp]
+        _lib.go_combine.restype = None
         _lib.go_metric_window.argtypes = [u32, u32, u32, vp, u64, u32, u32, vp, vp, vp, vp]
         _lib.go_metric_window.restype = None
         _lib.go_score_ring.argtypes = [u32, vp, u64, u32, ctypes.c_float, vp]
@@ -280,6 +282,15 @@ class MetricPersistence:
     pmask: np.ndarray   # [n] u8, bit m = metric m persistent at the last step
     flag: np.ndarray    # [n] u8 at the last step
     first: np.ndarray   # [n] i32 first flagged step or -1
+
+
+def combine(mask: np.ndarray, primary: int, min_signals: int) -> np.ndarray:
+    """Anomaly words [T][ceil(n/64)] u64 of the per-step multi-signal rule on exceed bytes mask[T][n]."""
+    mask = np.ascontiguousarray(mask, np.uint8)
+    T, n = mask.shape
+    out = np.zeros((T, (n + 63) // 64), np.uint64)
+    _load().go_combine(n, primary, min_signals, _ptr(mask), T, _ptr(out))
+    return out
 
 
 def metric_window(mask: np.ndarray, primary: int, min_signals: int, W: int, k: int) -> MetricPersistence:

@@ -390,6 +390,24 @@ void go_sweep(uint32_t n_nodes, const float* flops, const float* bw, float tol_c
     }
 }
 
+// Rule "combine" on its own (Section 4.2: several indicators must deviate, the
+// primary one -- training step time -- among them): from exceed bytes mask[T][n]
+// (bit m = metric m exceeds) to the anomaly words anom[T][ceil(n/64)] that go_score
+// itself writes: bit set iff bit `primary` is set and at least min_signals bits are.
+void go_combine(uint32_t n, uint32_t primary, uint32_t min_signals, const uint8_t* mask, uint64_t T,
+                uint64_t* anom) {
+    const size_t words = ((size_t)n + 63) / 64;
+    for (uint64_t t = 0; t < T; ++t) {
+        for (size_t w = 0; w < words; ++w) anom[t * words + w] = 0;
+        for (uint32_t i = 0; i < n; ++i) {
+            const uint8_t b = mask[t * n + i];
+            uint32_t set = 0;
+            for (int m = 0; m < 8; ++m) set += (b >> m) & 1u;
+            if (((b >> primary) & 1u) && set >= min_signals) anom[t * words + i / 64] |= 1ull << (i % 64);
+        }
+    }
+}
+
 // Persistence kept per indicator (the other reading of "multiple performance
 // indicators ... sustained across consecutive evaluation windows", Section 4.2:
 // each indicator must itself be sustained, and the indicators are combined

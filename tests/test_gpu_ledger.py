@@ -22,23 +22,6 @@ def say(*a):
     sys.stdout.flush()
 
 
-def pack_bits(bits):
-    T, n = bits.shape
-    words = np.zeros((T, (n + 63) // 64), np.uint64)
-    for i in range(n):
-        words[:, i // 64] |= bits[:, i].astype(np.uint64) << np.uint64(i % 64)
-    return words
-
-
-def combined(mask, p):
-    """The per-step multi-signal rule on exceed bytes (an input transformation of the
-    test: the default rule's anomaly bit as the scoring step defines it)."""
-    pc = np.zeros(mask.shape, np.uint8)
-    for m in range(8):
-        pc += (mask >> np.uint8(m)) & np.uint8(1)
-    return (((mask >> np.uint8(p.primary)) & 1) > 0) & (pc >= p.min_signals)
-
-
 def oracle_ledger(p, exceed, node_mask, node_anom_words, node_z, quant, horizon, limit, topk_k,
                   ranks=None, nodes=None):
     """What the ledger must hold after the whole history (optionally only for some
@@ -100,6 +83,7 @@ def feed(det, exceed, node_mask, node_z, batches):
 
 CASES = [
     # R, M, W, k, T, batches (None = one call), horizon, limit
+    (8, 2, 3, 2, 40, [7, 33], 10, 2),                       # one node
     (64, 1, 4, 3, 50, None, 30, 2),
     (64, 2, 1, 1, 20, [1] * 20, 5, 1),
     (72, 3, 20, 15, 600, None, 200, 3),                     # 256-step chunks: 3 of them
@@ -117,16 +101,16 @@ CASES = [
 def test_ledger_on_synthetic_histories(R, M, W, k, T, batches, horizon, limit):
     say(f"case ledger R={R} M={M} W={W} k={k} T={T} batches={batches}")
     N = R // 8
-    p = oracle_params(R=R, M=M, W=W, k=k, primary=min(1, M - 1), min_signals=min(2, M),
+    p = oracle_params(R=R, M=M, W=W, k=k, primary=(W + T) % M, min_signals=min(2, M),
                       directions=(1,) * M)
     seed = R + 13 * W + T
     long_bursts = (max(2, W // 2), 3 * W + 5)
     exceed = exceed_history(seed, T, R, M, 0.03, burst_items=max(4, R // 20), burst_len=long_bursts,
-                            gap_len=(1, 2 * W + 3))
+                            gap_len=(1, 2 * W + 3), burst_metrics=M)
     node_mask = exceed_history(seed + 1, T, N, M, 0.03, burst_items=max(3, N // 3), burst_len=long_bursts,
-                               gap_len=(1, 2 * W + 3))
+                               gap_len=(1, 2 * W + 3), burst_metrics=M)
     node_z = node_score_history(seed, T, N, scale=3.0)
-    node_anom = pack_bits(combined(node_mask, p))
+    node_anom = oracle.combine(node_mask, p.primary, p.min_signals)
     topk_k = min(64, N)
     want = oracle_ledger(p, exceed, node_mask, node_anom, node_z, 64.0, horizon, limit, topk_k)
     det = detector_for(p)
@@ -148,7 +132,7 @@ def test_ledger_quantisation_steps():
     p = oracle_params(R=R, M=M, W=W, k=8, directions=(1, 1))
     exceed = exceed_history(5, T, R, M, 0.2)
     node_mask = exceed_history(6, T, N, M, 0.3)
-    node_anom = pack_bits(combined(node_mask, p))
+    node_anom = oracle.combine(node_mask, p.primary, p.min_signals)
     for quant, scale in ((1.0, 50.0), (4096.0, 1.0), (0.125, 1e4), (64.0, 1e6)):
         node_z = node_score_history(int(quant * 8) + 1, T, N, scale=scale, outliers=0.2)
         want = oracle_ledger(p, exceed, node_mask, node_anom, node_z, quant, 50, 3, N)
@@ -200,7 +184,7 @@ def test_ledger_at_the_benchmark_size():
     exceed = exceed_history(31, T, R, M, 0.014, burst_items=600, burst_len=(150, 900), gap_len=(20, 500))
     node_mask = exceed_history(32, T, N, M, 0.014, burst_items=300, burst_len=(150, 900), gap_len=(20, 500))
     node_z = node_score_history(33, T, N, scale=2.0)
-    node_anom = pack_bits(combined(node_mask, p))
+    node_anom = oracle.combine(node_mask, p.primary, p.min_signals)
     rng = np.random.default_rng(9)
     ranks = np.sort(rng.choice(R, 2048, replace=False))
     ranks[:3] = [0, 1, 2]; ranks[-1] = R - 1

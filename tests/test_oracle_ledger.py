@@ -26,6 +26,33 @@ def pack_bits(bits):
     return words
 
 
+# ---- the per-step rule on exceed bytes ------------------------------------------------
+
+def test_combine_reproduces_the_anomaly_words_of_the_scoring_oracle():
+    """go_score applies the rule while it scores (pinned there on constructed cases); the
+    stand-alone version must give the same words from the same bytes."""
+    rng = np.random.default_rng(8)
+    for M, primary, min_signals in ((4, 0, 2), (3, 2, 1), (8, 5, 4), (1, 0, 1)):
+        p = oracle.Params(R=136, M=M, W=4, k=2, thr=0.3, primary=primary, min_signals=min_signals,
+                          directions=(1, -1, 0, 1, 1, -1, 0, 1)[:M])
+        x = np.exp(0.1 * rng.standard_normal((7, M, 136))).astype(np.float32)
+        s = oracle.score(p, x, want_z=False)
+        assert s.exceed_mask.any() and s.rank_anom.any()
+        assert np.array_equal(oracle.combine(s.exceed_mask, primary, min_signals), s.rank_anom)
+        assert np.array_equal(oracle.combine(s.node_mask, primary, min_signals), s.node_anom)
+
+
+def test_combine_by_hand():
+    byte = np.array([[0b0000, 0b0001, 0b0010, 0b0011, 0b0110, 0b0111, 0b1111] + [0] * 60 + [0b0101]], np.uint8)
+    w = oracle.combine(byte, 0, 2)            # needs bit 0 and one more
+    assert w.shape == (1, 2)
+    assert int(w[0, 0]) == (1 << 3) | (1 << 5) | (1 << 6) and int(w[0, 1]) == 1 << 3
+    w = oracle.combine(byte, 1, 3)            # needs bit 1 and two more
+    assert int(w[0, 0]) == (1 << 5) | (1 << 6) and int(w[0, 1]) == 0
+    w = oracle.combine(byte, 2, 1)            # bit 2 alone is enough
+    assert int(w[0, 0]) == (1 << 4) | (1 << 5) | (1 << 6) and int(w[0, 1]) == 1 << 3
+
+
 # ---- persistence per indicator ------------------------------------------------------
 
 @pytest.mark.parametrize("W,k", [(1, 1), (5, 3), (16, 16), (40, 7)])
