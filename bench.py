@@ -176,8 +176,8 @@ def main() -> int:
                     help="also run a plain 2 GiB elementwise copy kernel (known traffic) for counter calibration")
     a = ap.parse_args()
     if a.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus must be 1 "
-              "(the path shards by step across GPUs by design only)", file=sys.stderr)
+        print("bench.py: the library runs on one GPU; --gpus must be 1 "
+              "(sharding by step across GPUs exists as a design only)", file=sys.stderr)
         return 2
     import torch
     from workloads import generate, workload

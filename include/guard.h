@@ -273,9 +273,13 @@ gd_status gd_bind_ledger(gd_handle h, const gd_ledger_config* cfg, void* d_ledge
 
 /*
  * Takes the T steps gd_score_batch just scored into the ledger.
- *   d_exceed_mask [T][R] u8, d_node_mask [T][N] u8, d_node_z [T][N] f32: its outputs
+ *   d_exceed_mask [T][R] u8 (4-byte aligned), d_node_mask [T][N] u8, d_node_z [T][N] f32:
+ *                     its outputs, read only
  *   first_step_index: index of the batch's first step; batches must arrive in order
- *                     and first_step_index + T must stay below 2^31
+ *                     (each starting where the one before ended) and first_step_index + T
+ *                     must stay below 2^31
+ * Two kernels are enqueued on the stream; part of the ledger buffer serves as their work
+ * area, so two calls on one ledger must not overlap.
  * T == 0 is GD_OK and does nothing; T > max_T is GD_ERR_INVALID_ARG.  Independent of
  * gd_update_window: either may be called without the other, in any order.
  */
