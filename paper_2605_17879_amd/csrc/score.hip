@@ -1181,37 +1181,26 @@ bool use_split(const gd_score_args& a, int n_cu) {
            a.R % 32 == 0 && ((uintptr_t)a.node_mask & 3) == 0;
 }
 
-template <int NT, int ROWS, int LOG_NB, bool FULL>
-hipError_t launch_one(const gd_score_args& a, hipStream_t s) {
+template <int NT, int ROWS, int LOG_NB>
+constexpr size_t lds_bytes() {
     using SH = Shared<NT, LOG_NB, NT * 4 * ROWS / 8>;
-    constexpr size_t lds = ((sizeof(SH) + 15) & ~(size_t)15) + (size_t)ROWS * NT * 4;
+    return ((sizeof(SH) + 15) & ~(size_t)15) + (size_t)ROWS * NT * 4;
+}
+
+// A whole batch: enough workgroups to fill every CU once (as many as fit by LDS and
+// wave slots); each takes a contiguous run of ceil(T / grid) steps.
+template <int NT, int ROWS, int LOG_NB, bool FULL>
+hipError_t launch_runs(const gd_score_args& a, int n_cu, hipStream_t s) {
+    constexpr size_t lds = lds_bytes<NT, ROWS, LOG_NB>();
     static_assert(lds <= 160 * 1024, "LDS budget of one CU");
     auto kern = score_kernel<NT, ROWS, LOG_NB, FULL, false>;
-    auto kern_split = score_kernel<NT, ROWS, LOG_NB, FULL, true>;
     static bool configured = false;      // a handle is single-threaded; a repeated set is harmless
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_split),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipError_t cu_err;
-    const int n_cu = compute_units(&cu_err);
-    if (cu_err != hipSuccess) return cu_err;
-    if (use_split(a, n_cu)) {
-        const size_t n_exceed = (size_t)a.T * a.R / 4, n_node = (size_t)a.T * a.N / 4;
-        hipLaunchKernelGGL(zero_masks_kernel, dim3((uint32_t)((n_exceed + 255) / 256)), dim3(256), 0, s,
-                           reinterpret_cast<uint32_t*>(a.exceed_mask), n_exceed,
-                           reinterpret_cast<uint32_t*>(a.node_mask), n_node);
-        hipLaunchKernelGGL(kern_split, dim3(a.T * a.M), dim3(NT), lds, s, a);
-        hipLaunchKernelGGL(combine_kernel, dim3((a.R / 4 + 255) / 256, a.T), dim3(256), 0, s, a);
-        return hipGetLastError();
-    }
-    // Enough workgroups to fill every CU once (as many as fit by LDS and wave
-    // slots); each takes a contiguous run of ceil(T / grid) steps.
     const size_t by_lds = (size_t)160 * 1024 / lds, by_waves = (size_t)16 / (NT / WAVE);
     const size_t per_cu = by_lds < by_waves ? (by_lds ? by_lds : 1) : by_waves;
     const size_t cap = (size_t)n_cu * per_cu;
@@ -1220,10 +1209,41 @@ hipError_t launch_one(const gd_score_args& a, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <int NT, int ROWS, int LOG_NB>
+// A short batch: one workgroup per column between the fill and the combining kernel.
+template <int NT, int ROWS, int LOG_NB, bool FULL>
+hipError_t launch_columns(const gd_score_args& a, hipStream_t s) {
+    constexpr size_t lds = lds_bytes<NT, ROWS, LOG_NB>();
+    static_assert(lds <= 160 * 1024, "LDS budget of one CU");
+    auto kern = score_kernel<NT, ROWS, LOG_NB, FULL, true>;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const size_t n_exceed = (size_t)a.T * a.R / 4, n_node = (size_t)a.T * a.N / 4;
+    hipLaunchKernelGGL(zero_masks_kernel, dim3((uint32_t)((n_exceed + 255) / 256)), dim3(256), 0, s,
+                       reinterpret_cast<uint32_t*>(a.exceed_mask), n_exceed,
+                       reinterpret_cast<uint32_t*>(a.node_mask), n_node);
+    hipLaunchKernelGGL(kern, dim3(a.T * a.M), dim3(NT), lds, s, a);
+    hipLaunchKernelGGL(combine_kernel, dim3((a.R / 4 + 255) / 256, a.T), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// NT x ROWS: the tiling of a batch; CNT x CROWS: that of the per-column route, where a
+// column has the CU to itself and is spread over more threads (fewer rows per lane:
+// shorter passes between the barriers).
+template <int NT, int ROWS, int LOG_NB, int CNT = NT, int CROWS = ROWS, int CLOG_NB = LOG_NB>
 hipError_t launch(const gd_score_args& a, hipStream_t s) {
-    if (a.R == (uint32_t)NT * 4 * ROWS) return launch_one<NT, ROWS, LOG_NB, true>(a, s);
-    return launch_one<NT, ROWS, LOG_NB, false>(a, s);
+    static_assert(NT * ROWS == CNT * CROWS, "both tilings hold the same number of ranks");
+    hipError_t cu_err;
+    const int n_cu = compute_units(&cu_err);
+    if (cu_err != hipSuccess) return cu_err;
+    const bool full = a.R == (uint32_t)NT * 4 * ROWS;
+    if (use_split(a, n_cu))
+        return full ? launch_columns<CNT, CROWS, CLOG_NB, true>(a, s) : launch_columns<CNT, CROWS, CLOG_NB, false>(a, s);
+    return full ? launch_runs<NT, ROWS, LOG_NB, true>(a, n_cu, s) : launch_runs<NT, ROWS, LOG_NB, false>(a, n_cu, s);
 }
 
 }  // namespace
@@ -1248,8 +1268,8 @@ hipError_t gd_launch_score(const gd_score_args& a, hipStream_t s) {
     // (the 256-thread tilings take 2048 buckets: four workgroups then share a CU's LDS, and
     // their barrier-bound phases overlap)
     if (R <= 4096) return launch<256, 4, 11>(a, s);
-    if (R <= 16384) return launch<256, 16, 11>(a, s);
-    if (R <= 32768) return launch<512, 16, 12>(a, s);
+    if (R <= 16384) return launch<256, 16, 11, 1024, 4, 12>(a, s);
+    if (R <= 32768) return launch<512, 16, 12, 1024, 8, 12>(a, s);
     if (R <= 65536) return launch<1024, 16, 12>(a, s);
     return hipErrorInvalidValue;
 }
