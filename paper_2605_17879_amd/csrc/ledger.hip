@@ -14,13 +14,14 @@
 // ledger_count_kernel: one thread per item (a node, or four ranks) and per chunk
 // of steps.  The per-metric counts live in four registers as eight 16-bit fields,
 // biased so that a field's top bit says "reached k"; a step adds the entering
-// byte's bits and takes off the leaving byte's through a 256-entry table in LDS
-// (byte -> eight fields), and the rule itself is evaluated only while the primary
-// metric's top bit is on and no flagged step has been found yet.  A chunk other than the first rebuilds its
-// starting counts from the W steps before it, so chunks are independent; the
-// first flagged step is the minimum over chunks (an atomic max on 0xFFFFFFFF -
-// step).  For nodes the kernel also follows the default rule's own flag and
-// leaves one bit per (step, node) where an episode starts.
+// byte's bits and takes off the leaving byte's through a table in LDS (byte ->
+// eight fields, and the same words negated), and the rule itself is evaluated
+// only while the primary metric's top bit is on and no flagged step has been
+// found yet.  A chunk other than the first rebuilds its starting counts from the
+// W steps before it, so chunks are independent; the first flagged step is the
+// minimum over chunks (an atomic max on 0xFFFFFFFF - step).  For nodes the kernel
+// also follows the default rule's own flag and leaves one bit per (step, node)
+// where an episode starts.
 // ledger_finish_kernel, launched behind it: the rings take the batch's last
 // steps, the score sums are brought up to date, and one thread per node walks the
 // episode starts in step order.
