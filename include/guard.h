@@ -122,20 +122,21 @@ gd_status gd_set_streaming_steps(gd_handle h, uint32_t max_steps);
  *                                       popcount(mask) >= min_signals
  *   d_node_z       out  [T][N]    f32   node score of the primary metric:
  *                                       node_scale*(((z0+z1)+(z2+z3))+((z4+z5)+(z6+z7)))
- *                                       over the node's signed scores (or their max)
+ *                                       over the node's signed scores (or their max,
+ *                                       a zero maximum reported as +0)
  *   d_node_mask    out  [T][N]    u8    bit m: node score of metric m > z_threshold
  *   d_node_anom    out  [T][NW]   u64   multi-signal rule applied to d_node_mask
  *
  * All arithmetic is IEEE fp32, one rounding per operation, -0 read as +0.
  * T == 0 is a valid no-op.  Every output except d_z is required.
-  *
+ *
  * Missing samples: a NaN in d_x is a sample that did not arrive (polled telemetry
  * does not always answer, Section 7.1).  It is left out of its column's median and
  * MAD, which are taken over the samples present (the middle one of an odd number);
  * its z is 0, it never exceeds and it adds 0 to its node's score.  A column with
  * no sample present reports med = MAD = NaN and no exceedance.  Infinities remain
  * unsupported input (no fault; that column's results are unspecified).
-*/
+ */
 gd_status gd_score_batch(gd_handle h, const float* d_x, uint32_t T, float* d_med, float* d_mad,
                          float* d_z, uint8_t* d_exceed_mask, uint64_t* d_rank_anom,
                          float* d_node_z, uint8_t* d_node_mask, uint64_t* d_node_anom,

@@ -196,6 +196,9 @@ void go_score(const go_config* c, const float* x, uint64_t T, float* med, float*
                 } else {
                     v = q[0];
                     for (size_t g = 1; g < G; ++g) v = std::max(v, q[g]);
+                    // the largest of zeros of both signs has no sign of its own: a zero
+                    // node score is reported as +0 (rule "order" reads -0 as +0 as well)
+                    v = canon(v);
                 }
                 nz[n] = v;
                 if (v > thr) NE[n] |= (uint8_t)(1u << m);

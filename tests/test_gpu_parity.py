@@ -50,6 +50,56 @@ def test_shapes_full_and_ragged(R, M, route):
     assert rep["z_bit_exact"]
 
 
+@pytest.mark.parametrize("seed", range(32))
+def test_random_configurations(seed):
+    """Seeded draws over the whole configuration space at once -- rank count, metrics,
+    window, threshold, directions, primary metric, number of signals, node rule and its
+    scale, floors, missing samples, signs, batch cuts and route -- each through the
+    whole path against the oracle."""
+    import gpu_harness
+    rng = np.random.default_rng(1000 + seed)
+    R = 8 * int(np.exp(rng.uniform(0, np.log(1200))))
+    M = int(rng.integers(1, 9))
+    T = int(rng.integers(3, 40))
+    W = int(rng.integers(1, 13))
+    k = int(rng.integers(1, W + 1))
+    dirs = tuple(int(d) for d in rng.choice([1, -1, 0], M))
+    kw = dict(R=R, M=M, W=W, k=k, thr=float(rng.choice([3.5, 2.0, 0.5, 0.0, -0.5, 6.0])), directions=dirs,
+              primary=int(rng.integers(0, M)), min_signals=int(rng.integers(1, M + 1)),
+              node_agg=int(rng.choice([oracle.NODE_SUM_SCALED, oracle.NODE_MAX])),
+              node_scale=float(rng.choice([8 ** -0.5, 0.125, 1.0])),
+              rel_floor=float(rng.choice([1e-6, 1e-2, 0.0])), abs_floor=float(rng.choice([1e-30, 1e-3])))
+    p = oracle_params(**kw)
+    g = torch.Generator().manual_seed(seed)
+    sigma = float(rng.choice([0.02, 0.2, 1e-4]))
+    x = torch.exp(sigma * torch.randn((T, M, R), generator=g, dtype=torch.float64))
+    for n in rng.choice(R // 8, size=min(3, R // 8), replace=False):        # slow nodes from some step on
+        x[int(rng.integers(0, T)):, :, 8 * n: 8 * n + 8] *= float(rng.uniform(1.05, 1.5))
+    x = x.to(torch.float32)
+    flavour = seed % 4
+    if flavour == 1:                                  # missing samples, scattered and by node
+        x[torch.rand((T, M, R), generator=g) < 0.03] = float("nan")
+        x[T // 2, 0, : 8 * max(1, R // 64)] = float("nan")
+    elif flavour == 2:                                # signs and both zeros
+        x = x - 1.0
+        x[0, 0, 0] = 0.0
+        x[0, 0, 1] = -0.0
+    elif flavour == 3:                                # heavy ties
+        x = torch.round(x * 8) / 8
+    cuts = sorted(set(rng.integers(1, T, size=int(rng.integers(0, 4))).tolist()))
+    chunks = [b - a for a, b in zip([0] + cuts, cuts + [T])]
+    gpu_harness.STREAMING_STEPS = [None, 0, 64][seed % 3]
+    say(f"case random seed={seed} R={R} M={M} T={T} W={W} k={k} chunks={chunks} flavour={flavour} "
+        f"route={gpu_harness.STREAMING_STEPS} {kw}")
+    try:
+        rep = run_and_compare(p, x, topk_k=min(int(rng.integers(1, 70)), R // 8), chunks=chunks,
+                              label=f"random{seed}")
+    finally:
+        gpu_harness.STREAMING_STEPS = None
+    say("  report", rep)
+    assert rep["z_bit_exact"]
+
+
 @pytest.mark.parametrize("kind", ADVERSARIAL_KINDS)
 @pytest.mark.parametrize("R", [64, 4096, 65536])
 def test_adversarial_columns(kind, R, route):

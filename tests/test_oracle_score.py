@@ -320,6 +320,29 @@ def test_node_max_rule_and_whole_node_sensitivity():
     assert np.array_equal(bits(sm.node_z_all), bits(want))
 
 
+def test_node_max_of_zeros_of_both_signs_is_plus_zero():
+    """Ranks that sit exactly on the median score +0, or -0 when the metric is
+    lower-is-worse; the largest of such zeros is reported as +0 whatever their order,
+    while the scaled sum keeps the sign that IEEE addition gives it."""
+    R = 32
+    x = np.full((1, 3, R), 2.0, np.float32)
+    x[0, :, 8:16] = [2.0, 2.0, 3.0, 2.0, 1.0, 2.0, 2.0, 2.0]       # node 1: some ranks off the median
+    x[0, :, 16:24] = [1.0, 1.5, 1.0, 1.0, 1.0, 1.0, 1.0, 1.0]      # node 2: all below the median
+    for dirs in ((1, -1, 0), (-1, 1, 0)):
+        pm = P(R, 3, node_agg=oracle.NODE_MAX, directions=dirs, min_signals=1)
+        sm = oracle.score(pm, x, want_node_all=True, want_z=True)
+        assert (sm.med == 2.0).all() and (sm.mad == 0.0).all()
+        for m, d in enumerate(dirs):
+            nz = sm.node_z_all[0, m]
+            assert bits(nz[0]) == 0 and bits(nz[3]) == 0          # all eight on the median: +0, never -0
+            zp = sm.z[0, m] if d > 0 else (-sm.z[0, m] if d < 0 else np.abs(sm.z[0, m]))
+            assert nz[1] == zp[8:16].max() and nz[2] == zp[16:24].max()
+        ps = P(R, 3, directions=dirs, min_signals=1)
+        ss = oracle.score(ps, x, want_node_all=True)
+        for m, d in enumerate(dirs):
+            assert bits(ss.node_z_all[0, m, 0]) == (0x80000000 if d < 0 else 0)
+
+
 def test_signed_scores_feed_the_node_sum():
     # a lower-is-worse metric: the node score uses -z, so a node whose GPUs all
     # run low gets a positive node score
