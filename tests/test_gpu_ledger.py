@@ -124,6 +124,46 @@ def test_ledger_on_synthetic_histories(R, M, W, k, T, batches, horizon, limit):
     det.close()
 
 
+def _random_ledger_case(seed):
+    rng = np.random.default_rng(5000 + seed)
+    R = 8 * int(np.exp(rng.uniform(0, np.log(700))))
+    N = R // 8
+    M = int(rng.integers(1, 9))
+    W = int(np.exp(rng.uniform(0, np.log(300))))
+    k = int(rng.integers(1, W + 1))
+    T = int(rng.integers(1, 900))
+    cuts = sorted(set(rng.integers(1, max(2, T), size=int(rng.integers(0, 5))).tolist()) - {T})
+    batches = [b - a for a, b in zip([0] + cuts, cuts + [T])]
+    horizon, limit = int(np.exp(rng.uniform(0, np.log(2 * T + 2)))), int(rng.integers(1, 9))
+    quant = float(rng.choice([64.0, 1.0, 1000.0, 0.5]))
+    p = oracle_params(R=R, M=M, W=W, k=k, primary=int(rng.integers(0, M)), min_signals=int(rng.integers(1, M + 1)),
+                      directions=(1,) * M)
+    say(f"case random ledger seed={seed} R={R} M={M} W={W} k={k} T={T} batches={batches} horizon={horizon} "
+        f"limit={limit} quant={quant} primary={p.primary} min_signals={p.min_signals}")
+    rate = float(rng.choice([0.01, 0.1, 0.5]))
+    bursts = (max(1, W // 2), 3 * W + 5)
+    exceed = exceed_history(seed, T, R, M, rate, burst_items=max(1, R // 10), burst_len=bursts,
+                            gap_len=(1, 2 * W + 3), burst_metrics=M)
+    node_mask = exceed_history(seed + 7, T, N, M, rate, burst_items=max(1, N // 2), burst_len=bursts,
+                               gap_len=(1, 2 * W + 3), burst_metrics=M)
+    node_z = node_score_history(seed, T, N, scale=float(rng.choice([0.5, 5.0, 500.0])), outliers=0.05)
+    node_anom = oracle.combine(node_mask, p.primary, p.min_signals)
+    topk_k = int(rng.integers(1, N + 1))
+    want = oracle_ledger(p, exceed, node_mask, node_anom, node_z, quant, horizon, limit, topk_k)
+    det = detector_for(p, topk=topk_k)
+    det.alloc_ledger(max(batches), score_quant=quant, recur_horizon=horizon, recur_limit=limit)
+    feed(det, exceed, node_mask, node_z, batches)
+    compare_ledger(want, read_ledger(det, topk_k), f"random ledger {seed}")
+    det.close()
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_ledger_random_configurations(seed):
+    """Seeded draws over rank count, metrics, window, k, history length, batch cuts,
+    primary metric, number of signals, exceedance rate, horizon, limit and quantisation."""
+    _random_ledger_case(seed)
+
+
 def test_ledger_quantisation_steps():
     """Other quantisation steps, saturation on both sides and a fresh ledger read
     before anything was taken in."""

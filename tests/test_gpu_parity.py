@@ -50,17 +50,16 @@ def test_shapes_full_and_ragged(R, M, route):
     assert rep["z_bit_exact"]
 
 
-@pytest.mark.parametrize("seed", range(32))
-def test_random_configurations(seed):
-    """Seeded draws over the whole configuration space at once -- rank count, metrics,
-    window, threshold, directions, primary metric, number of signals, node rule and its
-    scale, floors, missing samples, signs, batch cuts and route -- each through the
-    whole path against the oracle."""
+def _random_case(seed, n_lo, n_hi, t_hi):
+    """One seeded draw over the whole configuration space at once -- rank count (n_lo to
+    n_hi nodes, log-uniform), metrics, window, threshold, directions, primary metric,
+    number of signals, node rule and its scale, floors, missing samples, signs, ties,
+    batch cuts and route -- through the whole path against the oracle."""
     import gpu_harness
     rng = np.random.default_rng(1000 + seed)
-    R = 8 * int(np.exp(rng.uniform(0, np.log(1200))))
+    R = 8 * int(np.exp(rng.uniform(np.log(n_lo), np.log(n_hi + 1))))
     M = int(rng.integers(1, 9))
-    T = int(rng.integers(3, 40))
+    T = int(rng.integers(3, t_hi + 1))
     W = int(rng.integers(1, 13))
     k = int(rng.integers(1, W + 1))
     dirs = tuple(int(d) for d in rng.choice([1, -1, 0], M))
@@ -98,6 +97,17 @@ def test_random_configurations(seed):
         gpu_harness.STREAMING_STEPS = None
     say("  report", rep)
     assert rep["z_bit_exact"]
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_random_configurations(seed):
+    _random_case(seed, 1, 1200, 39)
+
+
+@pytest.mark.parametrize("seed", range(100, 112))
+def test_random_configurations_of_many_ranks(seed):
+    """The same draws with 8 192 to 65 536 ranks: the large register tilings."""
+    _random_case(seed, 1024, 8192, 6)
 
 
 @pytest.mark.parametrize("kind", ADVERSARIAL_KINDS)
@@ -318,6 +328,44 @@ def test_device_division_is_correctly_rounded():
     rep = compare_scores(o, gpu, "division")
     assert rep["z_bit_exact"]
     det.close()
+
+
+def _random_severity_case(seed):
+    rng = np.random.default_rng(9000 + seed)
+    R = 8 * int(np.exp(rng.uniform(0, np.log(600))))
+    N, M = R // 8, int(rng.integers(1, 5))
+    W = int(np.exp(rng.uniform(0, np.log(400))))
+    T = int(rng.integers(1, 3 * W + 3))
+    k = int(rng.integers(1, W + 1))
+    dirs = tuple(int(d) for d in rng.choice([1, -1, 0], M))
+    p = oracle_params(R=R, M=M, W=W, k=k, thr=float(rng.choice([3.5, 1.0])), directions=dirs,
+                      primary=int(rng.integers(0, M)), min_signals=1)
+    say(f"case random severity seed={seed} R={R} M={M} W={W} T={T} k={k} dirs={dirs} primary={p.primary}")
+    g = torch.Generator().manual_seed(seed)
+    x = torch.exp(0.02 * torch.randn((T, M, R), generator=g, dtype=torch.float64))
+    for n in rng.choice(N, size=min(N, int(rng.integers(1, 6))), replace=False):
+        f = float(rng.uniform(1.03, 1.4)) ** float(rng.choice([1, -1]))
+        x[int(rng.integers(0, T)):, :, 8 * n: 8 * n + int(rng.integers(1, 9))] *= f
+    x = x.to(torch.float32)
+    if seed % 3 == 1:
+        x[torch.rand((T, M, R), generator=g) < 0.05] = float("nan")
+    d = oracle.detect(p, x.numpy(), topk_k=1)
+    det = detector_for(p)
+    out = gpu_score(det, x, want_z=False)
+    compare_scores(d["scores"], out, f"severity {seed}")
+    det.update_window(out, T)
+    moderate = float(rng.choice([0.10, 0.02, 0.0]))
+    rep = compare_severity(p, d, det, x, out, moderate, moderate + float(rng.choice([0.0, 0.05, 0.1])),
+                           label=f"severity {seed}")
+    det.close()
+    return rep
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_severity_random_configurations(seed):
+    """Seeded draws over rank count, window (1 to 400), history length around it, k,
+    directions, slowed and sped-up nodes and GPUs, missing samples and tier boundaries."""
+    _random_severity_case(seed)
 
 
 @pytest.mark.parametrize("R", [64, 4096, 65536])
