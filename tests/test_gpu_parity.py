@@ -635,16 +635,65 @@ def test_windows_of_whole_64_step_blocks(W, T, chunks):
     assert rep["rank_flags"] >= 1
 
 
+def _random_window_case(seed):
+    """gd_update_window / gd_flags / gd_topk_nodes on seeded random anomaly words and node
+    scores (not on scoring outputs), against the oracle's re-summed windows."""
+    rng = np.random.default_rng(3000 + seed)
+    R = 8 * int(np.exp(rng.uniform(0, np.log(2000))))
+    N = R // 8
+    W = int(rng.choice([int(np.exp(rng.uniform(0, np.log(1024)))), 64 * int(rng.integers(1, 17))]))
+    k = int(rng.integers(1, W + 1))
+    T = int(rng.integers(1, 3 * W + 70))
+    cuts = sorted(set(rng.integers(1, max(2, T), size=int(rng.integers(0, 4))).tolist()) - {T})
+    batches = [b - a for a, b in zip([0] + cuts, cuts + [T])]
+    say(f"case random window seed={seed} R={R} W={W} k={k} T={T} batches={batches}")
+    density = rng.choice([0.02, 0.3, 0.7, 0.97], size=(1, R))                 # per rank
+    rank_bits = rng.random((T, R)) < density
+    node_bits = rng.random((T, N)) < rng.choice([0.05, 0.5, 0.9], size=(1, N))
+
+    def pack(bits):
+        n = bits.shape[1]
+        padded = np.zeros((T, (n + 63) // 64 * 64), np.uint8)
+        padded[:, :n] = bits
+        return np.packbits(padded.reshape(T, -1, 64), axis=2, bitorder="little").view(np.uint64).reshape(T, -1)
+
+    ra, na = pack(rank_bits), pack(node_bits)
+    node_z = rng.standard_normal((T, N)).astype(np.float32)
+    node_z[rng.random((T, N)) < 0.3] = 0.25          # equal scores: ties in the ranking
+    p = oracle_params(R=R, M=1, W=W, k=k, min_signals=1)
+    pr, pn = oracle.window(R, ra, W, k), oracle.window(N, na, W, k)
+    topk_k = int(rng.integers(1, N + 1))
+    d = dict(ranks=pr, nodes=pn, node_flag_byte=oracle.node_flag_byte(8, pn.flag, pr.flag))
+    d["topk_idx"], d["topk_key"] = oracle.topk(pn.count, node_z[-1], topk_k)
+    det = detector_for(p, topk=topk_k)
+    dra, dna, dnz = (torch.from_numpy(a.view(np.int64) if a.dtype == np.uint64 else a).cuda() for a in (ra, na, node_z))
+    t0 = 0
+    for c in batches:
+        det.update_window(dict(rank_anom=dra[t0:t0 + c], node_anom=dna[t0:t0 + c], node_z=dnz[t0:t0 + c]), c)
+        t0 += c
+    compare_decision(p, d, det, topk_k, label=f"random window {seed}")
+    det.close()
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_window_random_configurations(seed):
+    _random_window_case(seed)
+
+
 @pytest.mark.parametrize("R,T", [(256, 9000), (1024, 9000), (4096, 2400), (16384, 2400), (65536, 800)])
 def test_hinted_runs_under_regime_changes(R, T):
+    _regime_case(R, T, R // 7 + T)
+
+
+def _regime_case(R, T, seed):
     """Long enough batches that every workgroup scores several consecutive steps and
     carries the previous step's median, reach and MAD over as hints -- on data whose
     level, spread and character keep changing from one step to the next: level jumps,
     spread collapsing to ties or exploding, two-valued and constant columns, signs,
     missing samples, then calm again."""
-    say(f"case regime changes R={R} T={T}")
+    say(f"case regime changes R={R} T={T} seed={seed}")
     M = 2
-    g = torch.Generator().manual_seed(R // 7 + T)
+    g = torch.Generator().manual_seed(seed)
     level = torch.ones(T, dtype=torch.float64)
     spread = torch.full((T,), 0.02, dtype=torch.float64)
     kind = torch.zeros(T, dtype=torch.int64)
