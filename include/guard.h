@@ -109,6 +109,20 @@ gd_status gd_bind_state(gd_handle h, void* d_state, size_t state_bytes);
 gd_status gd_set_streaming_steps(gd_handle h, uint32_t max_steps);
 
 /*
+ * Where one-step calls of gd_score_batch may start looking: d_med and d_mad are device
+ * arrays [n_metrics] holding the medians and MADs of a recent step -- normally the
+ * previous call's own d_med and d_mad outputs, which may be the very buffers the next
+ * call writes (each column reads its hint before it writes its result).  Telemetry
+ * moves little from one step to the next, so the selection then starts from a narrow
+ * bracket around the old median instead of sampling the column.  The arrays are read
+ * by later gd_score_batch calls with T == 1 and must stay valid until replaced; NULL,
+ * NULL switches the hints off.  Results never depend on the hints: a hint is only
+ * trusted as far as the counting pass confirms it, so stale, wrong or uninitialised
+ * contents cost time, not correctness.
+ */
+gd_status gd_set_streaming_hints(gd_handle h, const float* d_med, const float* d_mad);
+
+/*
  * Score T steps (Section 4.2: peer-relative evaluation, multi-signal rule with
  * step time primary; Section 7.1: 8-GPU nodes).  With N = R/8, RW = ceil(R/64),
  * NW = ceil(N/64):

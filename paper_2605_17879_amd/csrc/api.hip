@@ -17,6 +17,8 @@ struct gd_handle_s {
     gd_state_layout lay;
     uint8_t* d_state;
     uint32_t split_steps;
+    const float* hint_med;
+    const float* hint_mad;
     gd_ledger_config lcfg;
     gd_ledger_layout llay;
     uint8_t* d_led;
@@ -144,6 +146,8 @@ gd_status gd_create(const gd_config* c, gd_handle* out) {
     h->lay = make_layout(c->n_ranks, N, c->window);
     h->d_state = nullptr;
     h->split_steps = GD_DEFAULT_STREAMING_STEPS;
+    h->hint_med = nullptr;
+    h->hint_mad = nullptr;
     h->d_led = nullptr;
     h->led_max_T = 0;
     *out = h;
@@ -158,6 +162,17 @@ gd_status gd_destroy(gd_handle h) {
 gd_status gd_set_streaming_steps(gd_handle h, uint32_t max_steps) {
     if (!h) return GD_ERR_INVALID_ARG;
     h->split_steps = max_steps;
+    return GD_OK;
+}
+
+gd_status gd_set_streaming_hints(gd_handle h, const float* d_med, const float* d_mad) {
+    if (!h) return GD_ERR_INVALID_ARG;
+    if ((d_med == nullptr) != (d_mad == nullptr))
+        return fail(h, GD_ERR_INVALID_ARG, "gd_set_streaming_hints: give both arrays or neither");
+    if (((uintptr_t)d_med & 3) || ((uintptr_t)d_mad & 3))
+        return fail(h, GD_ERR_INVALID_ARG, "gd_set_streaming_hints: misaligned pointer");
+    h->hint_med = d_med;
+    h->hint_mad = d_mad;
     return GD_OK;
 }
 
@@ -196,6 +211,7 @@ gd_status gd_score_batch(gd_handle h, const float* d_x, uint32_t T, float* d_med
     a.primary = h->cfg.primary_metric; a.min_signals = h->cfg.min_signals;
     a.node_agg = h->cfg.node_agg;
     a.split_steps = h->split_steps;
+    a.hint_med = h->hint_med; a.hint_mad = h->hint_mad;
     a.thr = h->cfg.z_threshold; a.node_scale = h->cfg.node_scale;
     a.rel_floor = h->cfg.rel_floor; a.abs_floor = h->cfg.abs_floor;
     memcpy(a.dir, h->cfg.direction, 8);

@@ -22,6 +22,8 @@ struct gd_score_args {
     uint32_t T, R, M, N;
     uint32_t primary, min_signals, node_agg;
     uint32_t split_steps;  // batches of at most this many steps take one workgroup per column
+    const float* hint_med;  // [M] medians and
+    const float* hint_mad;  // [M] MADs of a recent step, or null: where a one-step call starts looking
     float thr, node_scale, rel_floor, abs_floor;
     int8_t dir[8];
 };

@@ -748,6 +748,20 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         sh.umax[0] = 0; sh.umax[1] = 0; sh.ncand = 0; sh.below = 0;
         sh.smin = 0xFFFFFFFFu; sh.smax = 0; sh.d1 = 0; sh.d2 = 0xFFFFFFFFu;
         for (int m = 0; m < 8; ++m) sh.hok[m] = 0;
+        // A one-step call may be told the medians and MADs of a recent step (usually the
+        // previous call's outputs).  They take the place of the hints a run of steps builds
+        // up for itself; like those they are only trusted as far as the counting pass
+        // confirms them, so any content is safe.
+        if (SPLIT && a.hint_med && a.hint_mad && a.T == 1) {
+            const float hm = a.hint_med[m_begin], hd = a.hint_mad[m_begin];
+            if (hm > 0.0f && hd > 0.0f && hm < 3.0e38f && hd < 3.0e38f) {      // (false for NaNs)
+                sh.hmed[m_begin] = hm;
+                sh.hwl[m_begin] = 1.25f * hd;
+                sh.hwh[m_begin] = 1.25f * hd;
+                sh.hmad[m_begin] = hd;
+                sh.hok[m_begin] = 1;
+            }
+        }
     }
     __syncthreads();
     // number of threads whose sampled element (row 0) is a real rank

@@ -25,7 +25,7 @@ EXPORTS = ("gd_default_config", "gd_create", "gd_destroy", "gd_state_bytes", "gd
            "gd_set_streaming_steps", "gd_score_batch", "gd_update_window", "gd_flags",
            "gd_topk_nodes", "gd_severity", "gd_sweep_score", "gd_probe_read", "gd_last_error",
            "gd_default_ledger_config", "gd_ledger_bytes", "gd_bind_ledger", "gd_update_ledger",
-           "gd_ledger_flags", "gd_topk_nodes_mean")
+           "gd_ledger_flags", "gd_topk_nodes_mean", "gd_set_streaming_hints")
 
 
 class GuardError(RuntimeError):
@@ -78,6 +78,8 @@ def load_library() -> ctypes.CDLL:
     lib.gd_bind_state.restype = ctypes.c_int
     lib.gd_set_streaming_steps.argtypes = [vp, u32]
     lib.gd_set_streaming_steps.restype = ctypes.c_int
+    lib.gd_set_streaming_hints.argtypes = [vp, vp, vp]
+    lib.gd_set_streaming_hints.restype = ctypes.c_int
     lib.gd_score_batch.argtypes = [vp, vp, u32] + [vp] * 9
     lib.gd_score_batch.restype = ctypes.c_int
     lib.gd_update_window.argtypes = [vp, vp, vp, vp, u32, u64, vp]
@@ -202,6 +204,12 @@ class Detector:
     def set_streaming_steps(self, max_steps: int):
         """Batches of at most max_steps steps are scored one workgroup per column (0: never)."""
         self._check(self.lib.gd_set_streaming_steps(self.h, max_steps))
+
+    def set_streaming_hints(self, med=None, mad=None):
+        """One-step calls start their selection from these [M] medians and MADs (device
+        tensors, typically the previous call's outputs; kept alive here)."""
+        self._hints = (med, mad)
+        self._check(self.lib.gd_set_streaming_hints(self.h, _p(med), _p(mad)))
 
     def alloc_outputs(self, T: int, want_z: bool = False) -> dict:
         """Output tensors of gd_score_batch for T steps (plain allocation)."""

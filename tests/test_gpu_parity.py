@@ -202,6 +202,58 @@ def test_streaming_configuration_prefix(route):
     assert rep["node_flags"] >= 1
 
 
+@pytest.mark.parametrize("R", [64, 1000, 4096, 16384, 32768, 40000, 65536])
+@pytest.mark.parametrize("source", ["previous outputs", "garbage"])
+def test_one_step_calls_with_hints(R, source):
+    """gd_set_streaming_hints: one-step calls that start from the previous call's medians
+    and MADs (the output buffers themselves), on data whose level and spread jump, collapse
+    to ties, change sign and lose samples between steps -- and calls whose hint arrays
+    hold arbitrary bit patterns.  Every output of every step against the oracle."""
+    say(f"case one-step hints R={R} {source}")
+    M, T = 3, 36
+    g = torch.Generator().manual_seed(R + len(source))
+    x = torch.exp(0.02 * torch.randn((T, M, R), generator=g, dtype=torch.float64))
+    x[:, 1] = 300.0 / x[:, 1]
+    x[8:] *= 1.5                      # level jump
+    x[12:14, 0] = 1.0                 # constant columns
+    x[16:18] = torch.round(x[16:18] * 16) / 16          # heavy ties
+    x[20:, 2] *= torch.exp(0.5 * torch.randn((T - 20, R), generator=g, dtype=torch.float64))   # spread explodes
+    x[24, 0, ::5] *= -1.0             # signs
+    x[26:28, 1, 3::7] = NAN           # missing samples
+    x[30:, :, 8:16] *= 1.2
+    x = x.to(torch.float32)
+    p = oracle_params(R=R, M=M, W=6, k=3, directions=(1, -1, 0), min_signals=1)
+    o = oracle.score(p, x.numpy(), want_z=True)
+    det = detector_for(p)
+    xd = x.cuda()
+    out = det.alloc_outputs(1, want_z=True)
+    if source == "previous outputs":
+        out["med"].fill_(float("nan")); out["mad"].fill_(float("nan"))
+        det.set_streaming_hints(out["med"].view(-1), out["mad"].view(-1))
+    else:
+        hm = torch.empty(M, dtype=torch.float32, device="cuda")
+        hd = torch.empty(M, dtype=torch.float32, device="cuda")
+        det.set_streaming_hints(hm, hd)
+    rng = np.random.default_rng(R)
+    for t in range(T):
+        if source == "garbage":       # any bit pattern, or plausible but wrong values
+            if t % 3 == 0:
+                bits = rng.integers(0, 2**32, size=2 * M, dtype=np.uint64).astype(np.uint32)
+                vals = bits.view(np.float32)
+            else:
+                vals = np.exp(rng.uniform(-3, 3, 2 * M)).astype(np.float32)
+            hm.copy_(torch.from_numpy(vals[:M].copy())); hd.copy_(torch.from_numpy(vals[M:].copy()))
+        det.score_batch(xd[t:t + 1], out)
+        torch.cuda.synchronize()
+        part = oracle.Scores(o.med[t:t + 1], o.mad[t:t + 1], o.z[t:t + 1], o.exceed_mask[t:t + 1],
+                             o.rank_anom[t:t + 1], o.node_z[t:t + 1], o.node_mask[t:t + 1],
+                             o.node_anom[t:t + 1], None, 0, 0)
+        rep = compare_scores(part, out, f"step {t}")
+        assert rep["z_bit_exact"]
+    det.set_streaming_hints(None, None)
+    det.close()
+
+
 def test_streaming_configuration_at_full_length():
     """Config 4 as specified: 100 000 steps of 32 768 ranks x 8 metrics, one step per call
     (W = 256, k = 200), the input made and consumed 1 000 steps at a time.  Against the
@@ -219,6 +271,7 @@ def test_streaming_configuration_at_full_length():
     sampled = set(rng.choice(w.T - w.W, 160, replace=False).tolist()) | set(range(w.T - w.W, w.T))
     CH = 1000
     out1, out_b = det.alloc_outputs(1, want_z=False), det_b.alloc_outputs(CH, want_z=False)
+    det.set_streaming_hints(out1["med"].view(-1), out1["mad"].view(-1))       # each call starts from the last one's
     kept_x, kept_out = {}, {}
     for c0 in range(0, w.T, CH):
         x = generate(w, seed=4, t0=c0, t1=c0 + CH, device="cuda")
