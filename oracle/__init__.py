@@ -15,7 +15,13 @@ top-k; for the severity tiers: exact rational arithmetic on small cases,
 both directions, tier boundaries; for missing samples (NaN): ``numpy.nanmedian``,
 exact rational arithmetic, and the same cluster without its silent nodes; for
 the single-node sweep: exact rational arithmetic, numpy medians, constructed
-throttling and asymmetry.  No function here is "parity unpinned".
+throttling and asymmetry; for the ledger (persistence per indicator, windowed
+score sums and their ranking, recurrence): the scoring oracle's own anomaly
+words for the stand-alone multi-signal rule, sliding sums by cumulative sums,
+the single-ring persistence where both rules coincide, a history on which they
+differ, scores that are whole multiples of the quantisation step, rounding and
+saturation cases, Python's sort, hand-built flag timelines.  No function here
+is "parity unpinned".
 """
 from __future__ import annotations
 
