@@ -50,7 +50,7 @@ def measured_traffic():
     return None
 
 
-VALU_PER_SAMPLE = 28.9      # SQ_INSTS_VALU x 64 / samples, profiles/score_kernel_c3_counters.txt
+VALU_PER_SAMPLE = 28.5      # SQ_INSTS_VALU x 64 / samples, profiles/score_kernel_c3_counters.txt
 SIMDS, CLOCK_HZ = 1024, 2.4e9
 
 
@@ -145,6 +145,24 @@ def detection_report(torch, det, w, x, out, fl) -> dict:
                                         "moderate": tiers[2], "severe": tiers[3]}}
 
 
+def z_variant(torch, det, w, x, stream, alg_bytes: int) -> dict:
+    """The scoring launch with the optional full z output (4 more bytes written per
+    sample): timed on its own, not part of `value`."""
+    out = det.alloc_outputs(w.T, want_z=True)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(4)]
+    with torch.cuda.stream(stream):
+        for s0, s1 in ev:
+            s0.record(stream)
+            det.score_batch(x, out, stream)
+            s1.record(stream)
+        torch.cuda.synchronize()
+    ms = sorted(s0.elapsed_time(s1) for s0, s1 in ev[1:])[1]
+    nbytes = alg_bytes + 4 * w.samples
+    del out
+    return {"what": "gd_score_batch writing z[T][M][R] as well", "ms": ms, "algorithmic_bytes": nbytes,
+            "GB/s": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+
 def ledger_leg(torch, det, w, out, stream) -> dict:
     """The bookkeeping beyond the default rule on the same resident scoring outputs
     (persistence per indicator, windowed score sums and their ranking, recurrence):
@@ -176,6 +194,8 @@ def main() -> int:
     ap.add_argument("--stream-steps", type=int, default=100000)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-stream", action="store_true", help="skip the streaming-latency leg")
+    ap.add_argument("--only-batch", action="store_true",
+                    help="only the timed batch steps and the read probe (for profiler runs): no CPU, streaming, z or ledger legs")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 2 GiB elementwise copy kernel (known traffic) for counter calibration")
     a = ap.parse_args()
@@ -245,7 +265,7 @@ def main() -> int:
         "config": {"workload": f"{w.R} ranks x {w.T} steps x {w.M} metrics fp32 "
                                f"(heavy-tailed noise, W={w.W}, k={w.k}, top-{w.topk}); "
                                "score_batch + update_window + flags + topk_nodes per step"},
-        "roofline": {"bound": "hbm", "kernel": "score_kernel<1024,16,12,true,false>", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "score_kernel<1024,16,12,true,false,false>", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(), "algorithmic_bytes": alg,
                      "avg_launch_ms": score_ms,
@@ -254,12 +274,14 @@ def main() -> int:
                      "issue_view": issue_view(w.samples, score_ms)},
     }
     res["detection"] = detection_report(torch, det, w, x, out, fl)
-    res["ledger"] = ledger_leg(torch, det, w, out, stream)
-    if not a.no_cpu:
+    if not a.only_batch:
+        res["with_z"] = z_variant(torch, det, w, x, stream, alg)
+        res["ledger"] = ledger_leg(torch, det, w, out, stream)
+    if not a.no_cpu and not a.only_batch:
         res["cpu_baseline"] = cpu_baseline(w, x, a.cpu_sample_steps)
     del x, out
     torch.cuda.empty_cache()
-    if not a.no_stream:
+    if not a.no_stream and not a.only_batch:
         res["streaming"] = streaming_latency(torch, a.stream_steps)
     det.close()
     print(json.dumps(res))

@@ -706,7 +706,7 @@ __device__ __forceinline__ void score_row_decide(const float (&x)[4], float xsta
 // per run of steps, so that the M columns of a step are scored side by side.  The
 // exceed bits of a column are then OR-ed into the (zeroed) mask outputs in global
 // memory and combine_kernel applies the multi-signal rule afterwards.
-template <int NT, int ROWS, int LOG_NB, bool FULL, bool SPLIT>
+template <int NT, int ROWS, int LOG_NB, bool FULL, bool SPLIT, bool WANT_Z>
 __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {   // <= 128 VGPRs: 16 waves per CU
     constexpr int BLK = NT * 4;               // ranks per register row
     constexpr int MAX_NODES = BLK * ROWS / 8;
@@ -948,17 +948,35 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         // The reciprocal route is exact while no intermediate can leave the normal
         // range: all x in [0, 2^59], 2^-34 <= med, 2^-60 <= s <= 2^60 (then every
         // non-zero |x - med| lies in [2^-59, 2^59]).
-        const bool fast = !special && a.node_agg == 0 && umax <= 0x5D000000u && med >= 0x1p-34f &&
-                          s >= 0x1p-60f && s <= 0x1p60f;
-        if (a.z) {   // optional full z output, recomputed so that the loops below stay lean
+        const bool exact_recip = !special && umax <= 0x5D000000u && med >= 0x1p-34f && s >= 0x1p-60f &&
+                                 s <= 0x1p60f;
+        const bool fast = exact_recip && a.node_agg == 0;
+        if (WANT_Z) {   // optional full z output, recomputed so that the loops below stay lean
                      // (it must come first: they refill the registers with the next column)
             float* zcol = a.z + (t * M + m) * (size_t)R;
+            // the quotient by the column's reciprocal and two residual corrections where that
+            // is exact (see score_row_fast; no sign bits there, so no -0 to read as +0)
+            const bool by_recip = opaque_s(exact_recip ? 1u : 0u) != 0u;
+            const float rz = 1.0f / s;
+            auto quotient = [&](float x) -> float {
+                const float d = x - med;
+                const float q0 = d * rz;
+                const float e0 = __builtin_fmaf(-q0, s, d);
+                const float q1 = __builtin_fmaf(e0, rz, q0);
+                const float e1 = __builtin_fmaf(-q1, s, d);
+                return __builtin_fmaf(e1, rz, q1);
+            };
 #pragma unroll
             for (int j = 0; j < ROWS; ++j) {
                 if (FULL || rbase(j, tz) < R) {
                     float4 q;
-                    q.x = ((v[j][0] + 0.0f) - med) / s; q.y = ((v[j][1] + 0.0f) - med) / s;
-                    q.z = ((v[j][2] + 0.0f) - med) / s; q.w = ((v[j][3] + 0.0f) - med) / s;
+                    if (by_recip) {
+                        q.x = quotient(v[j][0]); q.y = quotient(v[j][1]);
+                        q.z = quotient(v[j][2]); q.w = quotient(v[j][3]);
+                    } else {
+                        q.x = ((v[j][0] + 0.0f) - med) / s; q.y = ((v[j][1] + 0.0f) - med) / s;
+                        q.z = ((v[j][2] + 0.0f) - med) / s; q.w = ((v[j][3] + 0.0f) - med) / s;
+                    }
                     if (special) {              // a missing sample (NaN) scores 0
                         const uint32_t absm = opaque_s(0x7FFFFFFFu);
                         q.x = (__float_as_uint(v[j][0]) & absm) <= 0x7F800000u ? q.x : 0.0f;
@@ -1207,11 +1225,17 @@ template <int NT, int ROWS, int LOG_NB, bool FULL>
 hipError_t launch_runs(const gd_score_args& a, int n_cu, hipStream_t s) {
     constexpr size_t lds = lds_bytes<NT, ROWS, LOG_NB>();
     static_assert(lds <= 160 * 1024, "LDS budget of one CU");
-    auto kern = score_kernel<NT, ROWS, LOG_NB, FULL, false>;
+    auto kern = a.z ? score_kernel<NT, ROWS, LOG_NB, FULL, false, true>
+                    : score_kernel<NT, ROWS, LOG_NB, FULL, false, false>;
     static bool configured = false;      // a handle is single-threaded; a repeated set is harmless
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute(
+            reinterpret_cast<const void*>(score_kernel<NT, ROWS, LOG_NB, FULL, false, false>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(
+                reinterpret_cast<const void*>(score_kernel<NT, ROWS, LOG_NB, FULL, false, true>),
+                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
@@ -1228,11 +1252,17 @@ template <int NT, int ROWS, int LOG_NB, bool FULL>
 hipError_t launch_columns(const gd_score_args& a, hipStream_t s) {
     constexpr size_t lds = lds_bytes<NT, ROWS, LOG_NB>();
     static_assert(lds <= 160 * 1024, "LDS budget of one CU");
-    auto kern = score_kernel<NT, ROWS, LOG_NB, FULL, true>;
+    auto kern = a.z ? score_kernel<NT, ROWS, LOG_NB, FULL, true, true>
+                    : score_kernel<NT, ROWS, LOG_NB, FULL, true, false>;
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute(
+            reinterpret_cast<const void*>(score_kernel<NT, ROWS, LOG_NB, FULL, true, false>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(
+                reinterpret_cast<const void*>(score_kernel<NT, ROWS, LOG_NB, FULL, true, true>),
+                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
