@@ -26,7 +26,16 @@
 
 #include "gd_internal.h"
 
+// This file is compiled twice, side by side: as it is (every launch without the
+// optional z output, and the entry points) and, through score_z.hip, with
+// GD_SCORE_WANT_Z = 1 (the launches that write z as well).
+#ifndef GD_SCORE_WANT_Z
+#define GD_SCORE_WANT_Z 0
+#endif
+
 namespace {
+
+constexpr bool WANT_Z_HERE = GD_SCORE_WANT_Z != 0;
 
 constexpr int WAVE = 64;
 constexpr int CAND_CAP = 512;  // values ranked exactly in LDS per selection
@@ -951,19 +960,26 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         const bool exact_recip = !special && umax <= 0x5D000000u && med >= 0x1p-34f && s >= 0x1p-60f &&
                                  s <= 0x1p60f;
         const bool fast = exact_recip && a.node_agg == 0;
-        if (WANT_Z) {   // optional full z output, recomputed so that the loops below stay lean
+        // (the run-time test that is always true keeps the block a region of its own for the
+        // register allocator, as it was when the output pointer decided: without it this
+        // instantiation spills)
+        if (WANT_Z && opaque_s(1u) != 0u) {   // optional full z output, recomputed so that the loops below stay lean
                      // (it must come first: they refill the registers with the next column)
             float* zcol = a.z + (t * M + m) * (size_t)R;
             // the quotient by the column's reciprocal and two residual corrections where that
             // is exact (see score_row_fast; no sign bits there, so no -0 to read as +0)
             const bool by_recip = opaque_s(exact_recip ? 1u : 0u) != 0u;
-            const float rz = 1.0f / s;
+            // (optimiser-opaque copies of the median and the scale: the differences x - med of
+            // this loop must not be kept for the score loop below, 64 registers' worth)
+            const float medz = __uint_as_float(opaque_s(__float_as_uint(med)));
+            const float sz = __uint_as_float(opaque_s(__float_as_uint(s)));
+            const float rz = 1.0f / sz;
             auto quotient = [&](float x) -> float {
-                const float d = x - med;
+                const float d = x - medz;
                 const float q0 = d * rz;
-                const float e0 = __builtin_fmaf(-q0, s, d);
+                const float e0 = __builtin_fmaf(-q0, sz, d);
                 const float q1 = __builtin_fmaf(e0, rz, q0);
-                const float e1 = __builtin_fmaf(-q1, s, d);
+                const float e1 = __builtin_fmaf(-q1, sz, d);
                 return __builtin_fmaf(e1, rz, q1);
             };
 #pragma unroll
@@ -974,8 +990,8 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
                         q.x = quotient(v[j][0]); q.y = quotient(v[j][1]);
                         q.z = quotient(v[j][2]); q.w = quotient(v[j][3]);
                     } else {
-                        q.x = ((v[j][0] + 0.0f) - med) / s; q.y = ((v[j][1] + 0.0f) - med) / s;
-                        q.z = ((v[j][2] + 0.0f) - med) / s; q.w = ((v[j][3] + 0.0f) - med) / s;
+                        q.x = ((v[j][0] + 0.0f) - medz) / sz; q.y = ((v[j][1] + 0.0f) - medz) / sz;
+                        q.z = ((v[j][2] + 0.0f) - medz) / sz; q.w = ((v[j][3] + 0.0f) - medz) / sz;
                     }
                     if (special) {              // a missing sample (NaN) scores 0
                         const uint32_t absm = opaque_s(0x7FFFFFFFu);
@@ -986,6 +1002,7 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
                     }
                     *reinterpret_cast<float4*>(zcol + rbase(j, tz)) = q;
                 }
+                __builtin_amdgcn_sched_barrier(0);      // row by row: nothing of a later row starts early
             }
         }
         // Decision-only route for supporting one-sided metrics: find the exact boundary
@@ -1225,17 +1242,11 @@ template <int NT, int ROWS, int LOG_NB, bool FULL>
 hipError_t launch_runs(const gd_score_args& a, int n_cu, hipStream_t s) {
     constexpr size_t lds = lds_bytes<NT, ROWS, LOG_NB>();
     static_assert(lds <= 160 * 1024, "LDS budget of one CU");
-    auto kern = a.z ? score_kernel<NT, ROWS, LOG_NB, FULL, false, true>
-                    : score_kernel<NT, ROWS, LOG_NB, FULL, false, false>;
+    auto kern = score_kernel<NT, ROWS, LOG_NB, FULL, false, WANT_Z_HERE>;
     static bool configured = false;      // a handle is single-threaded; a repeated set is harmless
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(score_kernel<NT, ROWS, LOG_NB, FULL, false, false>),
-            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(
-                reinterpret_cast<const void*>(score_kernel<NT, ROWS, LOG_NB, FULL, false, true>),
-                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
@@ -1252,17 +1263,11 @@ template <int NT, int ROWS, int LOG_NB, bool FULL>
 hipError_t launch_columns(const gd_score_args& a, hipStream_t s) {
     constexpr size_t lds = lds_bytes<NT, ROWS, LOG_NB>();
     static_assert(lds <= 160 * 1024, "LDS budget of one CU");
-    auto kern = a.z ? score_kernel<NT, ROWS, LOG_NB, FULL, true, true>
-                    : score_kernel<NT, ROWS, LOG_NB, FULL, true, false>;
+    auto kern = score_kernel<NT, ROWS, LOG_NB, FULL, true, WANT_Z_HERE>;
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(score_kernel<NT, ROWS, LOG_NB, FULL, true, false>),
-            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(
-                reinterpret_cast<const void*>(score_kernel<NT, ROWS, LOG_NB, FULL, true, true>),
-                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
@@ -1290,7 +1295,27 @@ hipError_t launch(const gd_score_args& a, hipStream_t s) {
     return full ? launch_runs<NT, ROWS, LOG_NB, true>(a, n_cu, s) : launch_runs<NT, ROWS, LOG_NB, false>(a, n_cu, s);
 }
 
+// Pick the register tiling for R: NT threads x ROWS float4 rows hold NT*4*ROWS ranks.
+hipError_t pick_tiling(const gd_score_args& a, hipStream_t s) {
+    const uint32_t R = a.R;
+    if (R <= 256) return launch<64, 1, 10>(a, s);
+    if (R <= 1024) return launch<64, 4, 10>(a, s);
+    // (the 256-thread tilings take 2048 buckets: four workgroups then share a CU's LDS, and
+    // their barrier-bound phases overlap)
+    if (R <= 4096) return launch<256, 4, 11>(a, s);
+    if (R <= 16384) return launch<256, 16, 11, 1024, 4, 12>(a, s);
+    if (R <= 32768) return launch<512, 16, 12, 1024, 8, 12>(a, s);
+    if (R <= 65536) return launch<1024, 16, 12>(a, s);
+    return hipErrorInvalidValue;
+}
+
 }  // namespace
+
+#if GD_SCORE_WANT_Z
+
+hipError_t gd_launch_score_with_z(const gd_score_args& a, hipStream_t s) { return pick_tiling(a, s); }
+
+#else
 
 hipError_t gd_launch_read_probe(const float* d_x, uint64_t n_bytes, uint32_t* d_sink, hipStream_t s) {
     const uint64_t n_blocks = n_bytes / (256 * 1024);
@@ -1303,17 +1328,9 @@ hipError_t gd_launch_read_probe(const float* d_x, uint64_t n_bytes, uint32_t* d_
     return hipGetLastError();
 }
 
-// Pick the register tiling for R: NT threads x ROWS float4 rows hold NT*4*ROWS ranks.
 hipError_t gd_launch_score(const gd_score_args& a, hipStream_t s) {
     if (a.T == 0) return hipSuccess;
-    const uint32_t R = a.R;
-    if (R <= 256) return launch<64, 1, 10>(a, s);
-    if (R <= 1024) return launch<64, 4, 10>(a, s);
-    // (the 256-thread tilings take 2048 buckets: four workgroups then share a CU's LDS, and
-    // their barrier-bound phases overlap)
-    if (R <= 4096) return launch<256, 4, 11>(a, s);
-    if (R <= 16384) return launch<256, 16, 11, 1024, 4, 12>(a, s);
-    if (R <= 32768) return launch<512, 16, 12, 1024, 8, 12>(a, s);
-    if (R <= 65536) return launch<1024, 16, 12>(a, s);
-    return hipErrorInvalidValue;
+    return a.z ? gd_launch_score_with_z(a, s) : pick_tiling(a, s);
 }
+
+#endif
