@@ -688,18 +688,25 @@ def test_windows_of_whole_64_step_blocks(W, T, chunks):
     assert rep["rank_flags"] >= 1
 
 
-def _random_window_case(seed):
+def _random_window_case(seed, long_batches=False):
     """gd_update_window / gd_flags / gd_topk_nodes on seeded random anomaly words and node
-    scores (not on scoring outputs), against the oracle's re-summed windows."""
-    rng = np.random.default_rng(3000 + seed)
-    R = 8 * int(np.exp(rng.uniform(0, np.log(2000))))
+    scores (not on scoring outputs), against the oracle's re-summed windows.
+    long_batches: short windows and histories of many windows in few calls."""
+    rng = np.random.default_rng(3000 + seed + (500000 if long_batches else 0))
+    R = 8 * int(np.exp(rng.uniform(0, np.log(300 if long_batches else 2000))))
     N = R // 8
-    W = int(rng.choice([int(np.exp(rng.uniform(0, np.log(1024)))), 64 * int(rng.integers(1, 17))]))
+    if long_batches:
+        W = int(rng.choice([1, 3, 17, 64, 100, 128, 130, 192]))
+        T = int(rng.integers(4 * W + 600, 24 * W + 3000))
+    else:
+        W = int(rng.choice([int(np.exp(rng.uniform(0, np.log(1024)))), 64 * int(rng.integers(1, 17))]))
+        T = int(rng.integers(1, 3 * W + 70))
     k = int(rng.integers(1, W + 1))
-    T = int(rng.integers(1, 3 * W + 70))
     cuts = sorted(set(rng.integers(1, max(2, T), size=int(rng.integers(0, 4))).tolist()) - {T})
     batches = [b - a for a, b in zip([0] + cuts, cuts + [T])]
     say(f"case random window seed={seed} R={R} W={W} k={k} T={T} batches={batches}")
+    if long_batches and max(batches) <= max(4 * W, 512):
+        batches = [T]
     density = rng.choice([0.02, 0.3, 0.7, 0.97], size=(1, R))                 # per rank
     rank_bits = rng.random((T, R)) < density
     node_bits = rng.random((T, N)) < rng.choice([0.05, 0.5, 0.9], size=(1, N))
@@ -731,6 +738,11 @@ def _random_window_case(seed):
 @pytest.mark.parametrize("seed", range(24))
 def test_window_random_configurations(seed):
     _random_window_case(seed)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_window_random_long_batches(seed):
+    _random_window_case(seed, long_batches=True)
 
 
 @pytest.mark.parametrize("R,T", [(256, 9000), (1024, 9000), (4096, 2400), (16384, 2400), (65536, 800)])
