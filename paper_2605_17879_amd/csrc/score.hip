@@ -846,7 +846,7 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         const bool fused_umax = FULL && hinted;
         uint32_t* const umax_slot = &sh.umax[colpar];
         uint32_t umax = 0;
-        if (!fused_umax) {
+        if (__builtin_expect(!fused_umax, 0)) {
             uint32_t um = 0;
 #pragma unroll
             for (int j = 0; j < ROWS; ++j) {
@@ -903,7 +903,7 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         if (tid == 0) sh.umax[colpar ^ 1u] = 0;
         colpar ^= 1u;
         uint32_t present = R;
-        if (special) {
+        if (__builtin_expect(special, 0)) {
             if (tid == 0) sh.hok[m] = 0;
             __syncthreads();    // (a counting pass given up above has just reset sh.below)
             // samples present (padding lanes hold NaNs too): median and MAD are taken
@@ -935,7 +935,7 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
                 med = k0 == k1 ? float_of_key(s0) : 0.5f * (float_of_key(s0) + float_of_key(s1));
             }
         }
-        if (!have_mad && present)
+        if (__builtin_expect(!have_mad && present, 0))
             block_select<NT, ROWS, LOG_NB, false>(sh, DKeys<ROWS>{v, med},
                                                   __float_as_uint(fabsf(v[0][0] - med)),
                                                   svalid && v[0][0] == v[0][0], nsample, k0, k1, &s0, &s1);
@@ -1054,7 +1054,7 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
                 bool near;
                 if (rt == 0u) score_row_decide<false>(v[j], xstar, cc, kk, thr, margin, &e, &nz, &near);
                 else score_row_decide<true>(v[j], xstar, cc, kk, thr, margin, &e, &nz, &near);
-                if (__ballot(near)) {       // rare: settle the row with the exact chain
+                if (__builtin_expect(__ballot(near) != 0, 0)) {       // rare: settle the row with the exact chain
                     uint32_t e2;
                     score_row_fast<false>(v[j], med, ss, rs, thr, a.node_scale, &e2, &nz);
                 }
@@ -1062,7 +1062,7 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
                 score_row_fast<false>(v[j], med, ss, rs, thr, a.node_scale, &e, &nz);
             } else if (rt == 3u) {
                 score_row_fast<true>(v[j], med, ss, rs, thr, a.node_scale, &e, &nz);
-            } else if (rt == 4u) {
+            } else if (__builtin_expect(rt == 4u, 0)) {
                 score_row<0>(v[j], med, s, absmask, sgnmask, thr, a.node_scale, &e, &nz);
             } else {
                 score_row<1>(v[j], med, s, absmask, sgnmask, thr, a.node_scale, &e, &nz);
