@@ -25,6 +25,18 @@ def test_every_declared_symbol_is_exported():
         assert getattr(lib, n) is not None
 
 
+def test_header_is_plain_c(tmp_path):
+    """include/guard.h is the boundary: it must compile as C99 and as C++ on its own."""
+    import subprocess
+    src = tmp_path / "t.c"
+    src.write_text('#include "guard.h"\nint main(void) { gd_config c; gd_ledger_config l; (void)c; (void)l; return 0; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-c", str(src),
+                    "-o", str(tmp_path / "t.o")], check=True)
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-I", inc, "-x", "c++", "-c", str(src),
+                    "-o", str(tmp_path / "t2.o")], check=True)
+
+
 def make(**kw):
     lib = guard.load_library()
     c = guard.Config(n_ranks=kw.pop("R", 64), n_metrics=kw.pop("M", 2), window=kw.pop("W", 8),
