@@ -15,6 +15,11 @@
  *   gd_flags          the current fail-slow flags and counters;
  *   gd_topk_nodes     the k slowest nodes, ranked for the operator.
  *
+ * Around that path: gd_severity (how much a flagged node slows the job: the tiered
+ * response of Section 4.2), gd_sweep_score (scoring of single-node sweep results,
+ * Section 5), and the ledger calls (persistence kept per indicator, ranking by the
+ * score averaged over the window, recurrence of flag episodes as in Section 7).
+ *
  * The paper states the decision in words only.  The estimators and constants
  * used here (median / MAD x 1.4826 / threshold 3.5 / k-of-W / scaled node sum)
  * are the defaults written into gd_config below.
@@ -32,7 +37,8 @@
  *   - Inputs must be finite.  NaN or Inf in a column is tolerated (no fault, no
  *     out-of-bounds access) but that column's results are unspecified.
  *   - A handle is not thread safe.  gd_score_batch is stateless; only
- *     gd_update_window writes the bound state; gd_flags / gd_topk_nodes read it.
+ *     gd_update_window writes the bound state; gd_flags / gd_topk_nodes /
+ *     gd_severity read it; only gd_update_ledger writes the bound ledger.
  *   - The state is position independent: a byte copy of it, together with the
  *     number of steps consumed, is a checkpoint.
  */
