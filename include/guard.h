@@ -34,8 +34,9 @@
  *     caller has synchronised that stream.  No call synchronises the device.
  *   - Arguments are validated on the host before anything is launched; a call
  *     that returns an error has launched nothing.  No exception crosses the ABI.
- *   - Inputs must be finite.  NaN or Inf in a column is tolerated (no fault, no
- *     out-of-bounds access) but that column's results are unspecified.
+ *   - A NaN in the telemetry is a sample that did not arrive (see gd_score_batch).
+ *     An infinity is tolerated (no fault, no out-of-bounds access) but that
+ *     column's results are unspecified.
  *   - A handle is not thread safe.  gd_score_batch is stateless; only
  *     gd_update_window writes the bound state; gd_flags / gd_topk_nodes /
  *     gd_severity read it; only gd_update_ledger writes the bound ledger.
