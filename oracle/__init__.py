@@ -88,6 +88,8 @@ def _load():
                                      ctypes.c_float, ctypes.c_float, vp, vp]
         _lib.go_severity.restype = None
         u32, u64 = ctypes.c_uint32, ctypes.c_uint64
+        _lib.go_apply_membership.argtypes = [vp, u64, u32, u32, vp]
+        _lib.go_apply_membership.restype = None
         _lib.go_combine.argtypes = [u32, u32, u32, vp, u64, vp]
         _lib.go_combine.restype = None
         _lib.go_metric_window.argtypes = [u32, u32, u32, vp, u64, u32, u32, vp, vp, vp, vp]
@@ -288,6 +290,17 @@ class MetricPersistence:
     pmask: np.ndarray   # [n] u8, bit m = metric m persistent at the last step
     flag: np.ndarray    # [n] u8 at the last step
     first: np.ndarray   # [n] i32 first flagged step or -1
+
+
+def apply_membership(x: np.ndarray, active: np.ndarray) -> np.ndarray:
+    """A copy of x[T][M][R] with NaN wherever active[T][ceil(R/64)] (u64 bit words) says the
+    rank does not take part in the step."""
+    x = np.array(x, dtype=np.float32, order="C", copy=True)
+    T, M, R = x.shape
+    active = np.ascontiguousarray(active, np.uint64)
+    assert active.shape == (T, (R + 63) // 64)
+    _load().go_apply_membership(_ptr(x), T, M, R, _ptr(active))
+    return x
 
 
 def combine(mask: np.ndarray, primary: int, min_signals: int) -> np.ndarray:

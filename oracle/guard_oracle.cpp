@@ -411,6 +411,21 @@ void go_combine(uint32_t n, uint32_t primary, uint32_t min_signals, const uint8_
     }
 }
 
+// Elastic membership (ranks join and leave a job; polled telemetry does not always
+// answer, Section 7.1): active[T][ceil(R/64)] has bit r%64 of word r/64 set when rank
+// r takes part in step t.  A rank that does not is, for every metric of that step, a
+// sample that did not arrive: its value becomes the quiet NaN 0x7FC00000 (rule
+// "missing").  In place on x[T][M][R].
+void go_apply_membership(float* x, uint64_t T, uint32_t M, uint32_t R, const uint64_t* active) {
+    const size_t words = ((size_t)R + 63) / 64;
+    const uint32_t qnan = 0x7FC00000u;
+    for (uint64_t t = 0; t < T; ++t)
+        for (uint32_t m = 0; m < M; ++m)
+            for (uint32_t r = 0; r < R; ++r)
+                if (!((active[t * words + r / 64] >> (r % 64)) & 1ull))
+                    std::memcpy(&x[(t * M + m) * (uint64_t)R + r], &qnan, 4);
+}
+
 // Persistence kept per indicator (the other reading of "multiple performance
 // indicators ... sustained across consecutive evaluation windows", Section 4.2:
 // each indicator must itself be sustained, and the indicators are combined

@@ -119,3 +119,34 @@ def test_nothing_missing_is_the_old_behaviour():
         for m in range(2):
             assert s.med[t, m] == np.median(x[t, m])
             assert s.mad[t, m] == np.median(np.abs(x[t, m] - s.med[t, m]))
+
+
+def test_membership_mask_turns_absent_ranks_into_missing_samples():
+    """Against numpy: unpack the bit words, put NaN where the bit is clear; and scoring the
+    masked tensor is scoring the cluster without the absent nodes."""
+    rng = np.random.default_rng(12)
+    T, M, R = 5, 3, 136
+    x = np.exp(0.05 * rng.standard_normal((T, M, R))).astype(np.float32)
+    bits = rng.random((T, R)) < 0.8
+    bits[1] = True                      # a step with everybody
+    bits[3] = False                     # a step with nobody
+    padded = np.zeros((T, 192), np.uint8)
+    padded[:, :R] = bits
+    words = np.packbits(padded.reshape(T, 3, 64), axis=2, bitorder="little").view(np.uint64).reshape(T, 3)
+    y = oracle.apply_membership(x, words)
+    want = np.where(bits[:, None, :], x, np.float32("nan"))
+    assert np.array_equal(y.view(np.uint32) == 0x7FC00000, ~np.broadcast_to(bits[:, None, :], x.shape))
+    assert np.array_equal(np.isnan(y), np.isnan(want)) and np.array_equal(y[~np.isnan(y)], want[~np.isnan(want)])
+    assert not np.isnan(x).any()        # the input is left alone
+    # whole nodes absent from every step: the others score as a smaller cluster
+    absent = [3, 11]
+    act = np.ones((T, R), bool)
+    for n in absent:
+        act[:, 8 * n:8 * n + 8] = False
+    padded[:, :R] = act
+    words = np.packbits(padded.reshape(T, 3, 64), axis=2, bitorder="little").view(np.uint64).reshape(T, 3)
+    keep = np.array([r for r in range(R) if r // 8 not in absent])
+    a = oracle.score(params(R=R, M=M, directions=(1, 1, 1)), oracle.apply_membership(x, words), want_z=False)
+    b = oracle.score(params(R=R - 16, M=M, directions=(1, 1, 1)), np.ascontiguousarray(x[:, :, keep]), want_z=False)
+    assert np.array_equal(a.med.view(np.uint32), b.med.view(np.uint32))
+    assert np.array_equal(a.exceed_mask[:, keep], b.exceed_mask)
