@@ -206,6 +206,18 @@ gd_status gd_flags(gd_handle h, uint8_t* d_rank_flag, uint16_t* d_rank_count,
 gd_status gd_topk_nodes(gd_handle h, uint32_t k, int32_t* d_idx, uint64_t* d_key, void* stream);
 
 /*
+ * Elastic membership: marks the ranks that take no part in a step as missing samples
+ * of that step, in place, before gd_score_batch sees the batch.
+ *   d_x      in/out [T][M][R] f32 device, 16-byte aligned
+ *   d_active in     [T][ceil(R/64)] u64 device: bit r%64 of word r/64 set = rank r takes
+ *                   part in step t
+ * Where a bit is clear, x[t][m][r] becomes the quiet NaN 0x7FC00000 for every metric m
+ * (a missing sample: see gd_score_batch); nothing else is written.  T == 0 is a no-op;
+ * T above 65 535 per call is GD_ERR_INVALID_ARG.
+ */
+gd_status gd_apply_membership(gd_handle h, float* d_x, uint32_t T, const uint64_t* d_active, void* stream);
+
+/*
  * Severity of the performance impact of the flagged nodes (Section 4.2, the
  * tiered response: no observable impact / a moderate, sustained slowdown of
  * about 10% / severe degradation of 20% or more).  Call after gd_update_window

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libguard_hip.so")
-SOURCES = ["api.hip", "score.hip", "score_z.hip", "window.hip", "topk.hip", "severity.hip", "sweep.hip", "ledger.hip"]
+SOURCES = ["api.hip", "score.hip", "score_z.hip", "window.hip", "topk.hip", "severity.hip", "sweep.hip", "ledger.hip", "membership.hip"]
 
 # One rounding per written operation (no FMA contraction), IEEE divide,
 # denormals kept, and no packed-fp32 instructions.

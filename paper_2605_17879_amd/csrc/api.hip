@@ -279,6 +279,19 @@ gd_status gd_topk_nodes(gd_handle h, uint32_t k, int32_t* d_idx, uint64_t* d_key
     return GD_OK;
 }
 
+gd_status gd_apply_membership(gd_handle h, float* d_x, uint32_t T, const uint64_t* d_active, void* stream) {
+    if (!h) return GD_ERR_INVALID_ARG;
+    if (T == 0) return GD_OK;
+    if (!d_x || !d_active) return fail(h, GD_ERR_INVALID_ARG, "gd_apply_membership: null pointer");
+    if (((uintptr_t)d_x & 15) || ((uintptr_t)d_active & 7))
+        return fail(h, GD_ERR_INVALID_ARG, "gd_apply_membership: misaligned pointer");
+    if (T > 65535u) return fail(h, GD_ERR_INVALID_ARG, "gd_apply_membership: more than 65535 steps in one call");
+    hipError_t e = gd_launch_membership(d_x, d_active, T, h->cfg.n_ranks, h->cfg.n_metrics,
+                                        static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(h, e, "gd_apply_membership");
+    return GD_OK;
+}
+
 gd_status gd_severity(gd_handle h, const float* d_x, uint32_t T, const float* d_med, float moderate,
                       float severe, float* d_node_slowdown, uint8_t* d_node_tier, void* stream) {
     if (!h) return GD_ERR_INVALID_ARG;

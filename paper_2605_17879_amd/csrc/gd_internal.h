@@ -147,6 +147,8 @@ struct gd_sweep_args {
 hipError_t gd_launch_score(const gd_score_args& a, hipStream_t s);
 hipError_t gd_launch_score_with_z(const gd_score_args& a, hipStream_t s);   // score_z.hip
 hipError_t gd_launch_sweep(const gd_sweep_args& a, hipStream_t s);
+hipError_t gd_launch_membership(float* d_x, const uint64_t* d_active, uint32_t T, uint32_t R, uint32_t M,
+                                hipStream_t s);
 hipError_t gd_launch_severity(const gd_severity_args& a, hipStream_t s);
 hipError_t gd_launch_read_probe(const float* d_x, uint64_t n_bytes, uint32_t* d_sink, hipStream_t s);
 hipError_t gd_launch_window(const gd_window_args& a, hipStream_t s);

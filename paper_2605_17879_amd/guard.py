@@ -25,7 +25,7 @@ EXPORTS = ("gd_default_config", "gd_create", "gd_destroy", "gd_state_bytes", "gd
            "gd_set_streaming_steps", "gd_score_batch", "gd_update_window", "gd_flags",
            "gd_topk_nodes", "gd_severity", "gd_sweep_score", "gd_probe_read", "gd_last_error",
            "gd_default_ledger_config", "gd_ledger_bytes", "gd_bind_ledger", "gd_update_ledger",
-           "gd_ledger_flags", "gd_topk_nodes_mean", "gd_set_streaming_hints")
+           "gd_ledger_flags", "gd_topk_nodes_mean", "gd_set_streaming_hints", "gd_apply_membership")
 
 
 class GuardError(RuntimeError):
@@ -107,6 +107,8 @@ def load_library() -> ctypes.CDLL:
     lib.gd_ledger_flags.restype = ctypes.c_int
     lib.gd_topk_nodes_mean.argtypes = [vp, u32, vp, vp, vp]
     lib.gd_topk_nodes_mean.restype = ctypes.c_int
+    lib.gd_apply_membership.argtypes = [vp, vp, u32, vp, vp]
+    lib.gd_apply_membership.restype = ctypes.c_int
     lib.gd_last_error.argtypes = [vp]
     lib.gd_last_error.restype = ctypes.c_char_p
     _lib = lib
@@ -210,6 +212,13 @@ class Detector:
         tensors, typically the previous call's outputs; kept alive here)."""
         self._hints = (med, mad)
         self._check(self.lib.gd_set_streaming_hints(self.h, _p(med), _p(mad)))
+
+    def apply_membership(self, x, active, stream=None):
+        """NaN (missing) in place wherever active[T][ceil(R/64)] (int64 bit words) has a clear bit."""
+        T = x.shape[0]
+        assert x.is_cuda and x.is_contiguous() and tuple(x.shape) == (T, self.M, self.R)
+        assert active.is_cuda and active.is_contiguous() and tuple(active.shape) == (T, self.RW)
+        self._check(self.lib.gd_apply_membership(self.h, x.data_ptr(), T, active.data_ptr(), self._stream(stream)))
 
     def alloc_outputs(self, T: int, want_z: bool = False) -> dict:
         """Output tensors of gd_score_batch for T steps (plain allocation)."""

@@ -84,6 +84,10 @@ def test_state_size_and_argument_checks_without_a_device():
     assert lib.gd_sweep_score(h, None, 256, 3, 0.05, 0.1, 0.15, 256, 256, 256, 256, None) == 1
     assert lib.gd_sweep_score(h, None, None, 0, 0.05, 0.1, 0.15, None, None, None, None, None) == 0
     assert lib.gd_probe_read(h, None, 1 << 20, 256, None) == 1
+    assert lib.gd_apply_membership(h, None, 1, 256, None) == 1
+    assert lib.gd_apply_membership(h, 256 + 4, 1, 256, None) == 1   # x not 16-byte aligned
+    assert lib.gd_apply_membership(h, 256, 70000, 256, None) == 1
+    assert lib.gd_apply_membership(h, None, 0, None, None) == 0
     assert lib.gd_set_streaming_hints(h, 256, None) == 1        # both or neither
     assert lib.gd_set_streaming_hints(h, 256 + 2, 256) == 1     # misaligned
     assert lib.gd_set_streaming_hints(h, 256, 512) == 0

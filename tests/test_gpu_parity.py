@@ -582,6 +582,38 @@ def test_missing_samples(R, M, route):
         assert rep["z_bit_exact"]
 
 
+@pytest.mark.parametrize("R,M,T", [(8, 1, 3), (72, 2, 5), (1000, 3, 7), (4096, 8, 4), (65536, 2, 3)])
+def test_membership_mask(R, M, T):
+    """gd_apply_membership: the tensor after the call is, bit for bit, the oracle's (NaN
+    exactly where a rank takes no part, everything else untouched), and the batch scored
+    after it is the oracle's scoring of the oracle's masked tensor."""
+    say(f"case membership R={R} M={M} T={T}")
+    rng = np.random.default_rng(R + T)
+    g = torch.Generator().manual_seed(R)
+    x = torch.exp(0.02 * torch.randn((T, M, R), generator=g, dtype=torch.float64)).to(torch.float32)
+    x[:, :, :8] *= 1.3
+    bits = rng.random((T, R)) < 0.9
+    bits[0] = True                                  # everybody
+    if T > 2:
+        bits[2, : R // 2] = False                   # half of the cluster absent
+    bits[-1, 8 * (R // 16): 8 * (R // 16) + 8] = False   # a whole node
+    RW = (R + 63) // 64
+    padded = np.zeros((T, RW * 64), np.uint8)
+    padded[:, :R] = bits
+    words = np.packbits(padded.reshape(T, RW, 64), axis=2, bitorder="little").view(np.uint64).reshape(T, RW)
+    want = oracle.apply_membership(x.numpy(), words)
+    p = oracle_params(R=R, M=M, W=3, k=2, directions=(1,) * M, min_signals=1)
+    det = detector_for(p)
+    xd = x.cuda()
+    det.apply_membership(xd, torch.from_numpy(words.view(np.int64)).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(xd.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    o = oracle.score(p, want, want_z=True)
+    rep = compare_scores(o, gpu_score(det, xd, want_z=True), "after the mask")
+    assert rep["z_bit_exact"]
+    det.close()
+
+
 def test_severity_with_missing_samples():
     R, M, W, T = 1024, 2, 8, 20
     say("case severity with missing samples")
