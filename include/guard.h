@@ -322,6 +322,26 @@ gd_status gd_update_ledger(gd_handle h, const uint8_t* d_exceed_mask, const uint
                            void* stream);
 
 /*
+ * gd_update_ledger for callers that cannot allocate device memory or hand over a work
+ * area: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same results in the ledger, same two kernels; their work
+ * area (the episode-start map and the staged counts) is a static device array inside
+ * the library, gd_ledger_static_scratch_bytes() = 8 MiB per GPU, held from the first
+ * call on that GPU until the process ends.  The call itself allocates nothing, here or
+ * in any library it uses.  The ledger may therefore be bound with max_T = 1; T is
+ * limited by the array instead: align256(T * ceil(N/64) * 8) + 16 R + 18 N (rounded up
+ * to 256 per term) must not exceed it (T <= 5 800 at 65 536 ranks), else
+ * GD_ERR_INVALID_ARG and nothing is launched.
+ * Every call on one GPU, from any handle, shares that GPU's array: calls that could
+ * overlap there (different streams, different threads) race; calls on one stream do
+ * not.  Nothing in the array has to be cleared between calls.
+ */
+size_t gd_ledger_static_scratch_bytes(void);
+gd_status gd_update_ledger_static(gd_handle h, const uint8_t* d_exceed_mask, const uint8_t* d_node_mask,
+                                  const float* d_node_z, uint32_t T, uint64_t first_step_index,
+                                  void* stream);
+
+/*
  * Reads the ledger as of the last step taken in.  Every output is device memory
  * and may be NULL.
  *   d_rank_pmask [R] u8   bit m: metric m is sustained for the rank

@@ -371,22 +371,23 @@ gd_status gd_bind_ledger(gd_handle h, const gd_ledger_config* cfg, void* d_ledge
     return GD_OK;
 }
 
-gd_status gd_update_ledger(gd_handle h, const uint8_t* d_exceed_mask, const uint8_t* d_node_mask,
-                           const float* d_node_z, uint32_t T, uint64_t first_step_index,
-                           void* stream) {
-    if (!h) return GD_ERR_INVALID_ARG;
-    if (!h->d_led) return fail(h, GD_ERR_INVALID_ARG, "gd_update_ledger: no ledger bound");
-    if (T == 0) return GD_OK;
-    if (T > h->led_max_T)
-        return fail(h, GD_ERR_INVALID_ARG, "gd_update_ledger: T exceeds the max_T the ledger was bound with");
+namespace {
+
+// Checks and arguments shared by the two entry points that take a batch into the ledger.
+gd_status ledger_update_args(gd_handle h, const char* who, const uint8_t* d_exceed_mask,
+                             const uint8_t* d_node_mask, const float* d_node_z, uint32_t T,
+                             uint64_t first_step_index, gd_ledger_args* out) {
+    const std::string name(who);
     if (!d_exceed_mask || !d_node_mask || !d_node_z)
-        return fail(h, GD_ERR_INVALID_ARG, "gd_update_ledger: a required pointer is null");
+        return fail(h, GD_ERR_INVALID_ARG, name + ": a required pointer is null");
     if (((uintptr_t)d_exceed_mask & 3) || ((uintptr_t)d_node_z & 3))
-        return fail(h, GD_ERR_INVALID_ARG, "gd_update_ledger: misaligned pointer");
+        return fail(h, GD_ERR_INVALID_ARG, name + ": misaligned pointer");
     if (first_step_index + (uint64_t)T > 0x7FFFFFFFull)
-        return fail(h, GD_ERR_INVALID_ARG, "gd_update_ledger: step index beyond 2^31 - 1");
-    gd_ledger_args a;
+        return fail(h, GD_ERR_INVALID_ARG, name + ": step index beyond 2^31 - 1");
+    gd_ledger_args& a = *out;
     a.led = h->d_led; a.lay = h->llay;
+    a.rise = reinterpret_cast<uint64_t*>(h->d_led + h->llay.rise);
+    a.counts_new = h->d_led + h->llay.counts_new;
     a.exceed_mask = d_exceed_mask; a.node_mask = d_node_mask; a.node_z = d_node_z;
     a.T = T; a.R = h->cfg.n_ranks; a.N = h->N; a.W = h->cfg.window; a.K = h->cfg.persist_k;
     a.primary = h->cfg.primary_metric; a.min_signals = h->cfg.min_signals;
@@ -398,8 +399,51 @@ gd_status gd_update_ledger(gd_handle h, const uint8_t* d_exceed_mask, const uint
     a.limit = h->lcfg.recur_limit;
     a.quant = h->lcfg.score_quant;
     a.first_step = first_step_index; a.horizon = h->lcfg.recur_horizon;
+    return GD_OK;
+}
+
+}  // namespace
+
+gd_status gd_update_ledger(gd_handle h, const uint8_t* d_exceed_mask, const uint8_t* d_node_mask,
+                           const float* d_node_z, uint32_t T, uint64_t first_step_index,
+                           void* stream) {
+    if (!h) return GD_ERR_INVALID_ARG;
+    if (!h->d_led) return fail(h, GD_ERR_INVALID_ARG, "gd_update_ledger: no ledger bound");
+    if (T == 0) return GD_OK;
+    if (T > h->led_max_T)
+        return fail(h, GD_ERR_INVALID_ARG, "gd_update_ledger: T exceeds the max_T the ledger was bound with");
+    gd_ledger_args a;
+    const gd_status st = ledger_update_args(h, "gd_update_ledger", d_exceed_mask, d_node_mask, d_node_z, T,
+                                            first_step_index, &a);
+    if (st != GD_OK) return st;
     hipError_t e = gd_launch_ledger(a, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(h, e, "gd_update_ledger");
+    return GD_OK;
+}
+
+size_t gd_ledger_static_scratch_bytes(void) { return gd_ledger_static_bytes(); }
+
+gd_status gd_update_ledger_static(gd_handle h, const uint8_t* d_exceed_mask, const uint8_t* d_node_mask,
+                                  const float* d_node_z, uint32_t T, uint64_t first_step_index,
+                                  void* stream) {
+    if (!h) return GD_ERR_INVALID_ARG;
+    if (!h->d_led) return fail(h, GD_ERR_INVALID_ARG, "gd_update_ledger_static: no ledger bound");
+    if (T == 0) return GD_OK;
+    gd_ledger_args a;
+    const gd_status st = ledger_update_args(h, "gd_update_ledger_static", d_exceed_mask, d_node_mask,
+                                            d_node_z, T, first_step_index, &a);
+    if (st != GD_OK) return st;
+    bool fits = true;
+    hipError_t e = gd_launch_ledger_static(a, static_cast<hipStream_t>(stream), &fits);
+    if (!fits) {
+        char msg[200];
+        snprintf(msg, sizeof msg,
+                 "gd_update_ledger_static: %u steps of %u nodes need more than the %zu bytes of the "
+                 "library's static work area; send shorter batches",
+                 T, h->N, gd_ledger_static_bytes());
+        return fail(h, GD_ERR_INVALID_ARG, msg);
+    }
+    if (e != hipSuccess) return hip_fail(h, e, "gd_update_ledger_static");
     return GD_OK;
 }
 

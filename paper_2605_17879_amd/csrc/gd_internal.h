@@ -99,6 +99,11 @@ struct gd_ledger_layout {
 struct gd_ledger_args {
     uint8_t* led;
     gd_ledger_layout lay;
+    // The two spans that only serve the kernels of one call (not part of the ledger's
+    // contents): inside the caller's buffer at lay.rise / lay.counts_new, or in the
+    // library's own static device array for the entry point that may not allocate.
+    uint64_t* rise;               // [NW][T] episode starts found in the batch
+    uint8_t* counts_new;          // lay.counts_bytes: final counts of a batch cut into chunks
     const uint8_t* exceed_mask;   // [T][R]
     const uint8_t* node_mask;     // [T][N]
     const float* node_z;          // [T][N]
@@ -155,6 +160,10 @@ hipError_t gd_launch_window(const gd_window_args& a, hipStream_t s);
 hipError_t gd_launch_flags(const gd_flags_args& a, hipStream_t s);
 hipError_t gd_launch_topk(const gd_topk_args& a, hipStream_t s);
 hipError_t gd_launch_ledger(const gd_ledger_args& a, hipStream_t s);
+// The same launch with the work spans placed in the library's static device array;
+// *fits = false (and nothing launched) when the batch needs more than the array holds.
+hipError_t gd_launch_ledger_static(gd_ledger_args a, hipStream_t s, bool* fits);
+size_t gd_ledger_static_bytes();
 hipError_t gd_launch_ledger_flags(const gd_ledger_flags_args& a, hipStream_t s);
 
 #endif  // GD_INTERNAL_H_

@@ -93,7 +93,7 @@ __device__ __forceinline__ void count_items(const gd_ledger_args& a, uint32_t bl
     uint16_t* cnt = reinterpret_cast<uint16_t*>(a.led + (NODE ? a.lay.node_cnt : a.lay.rank_cnt));
     uint32_t* first = reinterpret_cast<uint32_t*>(a.led + (NODE ? a.lay.node_first : a.lay.rank_first));
     uint16_t* ccnt = reinterpret_cast<uint16_t*>(a.led + a.lay.node_ccnt);
-    uint64_t* rise = reinterpret_cast<uint64_t*>(a.led + a.lay.rise);
+    uint64_t* rise = a.rise;
     const uint32_t W = a.W, K = a.K, T = a.T;
     const uint32_t s0 = blockIdx.y * a.chunk;
     const uint32_t s1 = min(T, s0 + a.chunk);
@@ -187,16 +187,22 @@ __device__ __forceinline__ void count_items(const gd_ledger_args& a, uint32_t bl
     if (s1 == T) {
         // With several chunks the first one may still have to read the old counts:
         // the new ones go to the staging span and the finishing kernel moves them.
-        const size_t shift = gridDim.y > 1 ? (a.lay.counts_new - a.lay.rank_cnt) / 2 : 0;
+        // (the staging span is laid out like the span of counts itself)
+        const bool staged = gridDim.y > 1;
+        uint16_t* cnt_out = staged ? reinterpret_cast<uint16_t*>(
+                                         a.counts_new + ((NODE ? a.lay.node_cnt : a.lay.rank_cnt) - a.lay.rank_cnt))
+                                   : cnt;
+        uint16_t* ccnt_out = staged ? reinterpret_cast<uint16_t*>(a.counts_new + (a.lay.node_ccnt - a.lay.rank_cnt))
+                                    : ccnt;
 #pragma unroll
         for (int k = 0; k < IPT; ++k)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const uint32_t v = c[k][j] - bias;
-                cnt[shift + (size_t)field_metric(2 * j, a.primary) * n_items + i + k] = (uint16_t)(v & 0xFFFFu);
-                cnt[shift + (size_t)field_metric(2 * j + 1, a.primary) * n_items + i + k] = (uint16_t)(v >> 16);
+                cnt_out[(size_t)field_metric(2 * j, a.primary) * n_items + i + k] = (uint16_t)(v & 0xFFFFu);
+                cnt_out[(size_t)field_metric(2 * j + 1, a.primary) * n_items + i + k] = (uint16_t)(v >> 16);
             }
-        if (NODE) ccnt[shift + i] = (uint16_t)cc;
+        if (NODE) ccnt_out[i] = (uint16_t)cc;
     }
 }
 
@@ -254,7 +260,7 @@ __global__ __launch_bounds__(LED_NT) void ledger_finish_kernel(const gd_ledger_a
             nring[(size_t)((a.first_step + s) % W) * N + n] = a.node_mask[(size_t)s * N + n];
         }
         if (T > a.chunk) {       // the batch was cut into chunks: its final counts wait in the staging span
-            const uint32_t* from = reinterpret_cast<const uint32_t*>(a.led + a.lay.counts_new);
+            const uint32_t* from = reinterpret_cast<const uint32_t*>(a.counts_new);
             uint32_t* to = reinterpret_cast<uint32_t*>(a.led + a.lay.rank_cnt);
             for (size_t q = me; q < a.lay.counts_bytes / 4; q += stride) to[q] = from[q];
         }
@@ -297,7 +303,7 @@ __global__ __launch_bounds__(LED_NT) void ledger_finish_kernel(const gd_ledger_a
 
     // episode starts, in step order: lane l fetches the word of step s + l, and the few
     // words that hold a start are handed round
-    const uint64_t* rise = reinterpret_cast<const uint64_t*>(a.led + a.lay.rise);
+    const uint64_t* rise = a.rise;
     int32_t* starts = reinterpret_cast<int32_t*>(a.led + a.lay.node_starts);
     int32_t* term = reinterpret_cast<int32_t*>(a.led + a.lay.node_term);
     const uint32_t word = __builtin_amdgcn_readfirstlane(n / 64);
@@ -406,6 +412,45 @@ hipError_t gd_launch_ledger(const gd_ledger_args& a, hipStream_t s) {
     copy_blocks = copy_blocks < 1 ? 1 : (copy_blocks > 2048 ? 2048 : copy_blocks);
     hipLaunchKernelGGL(ledger_finish_kernel, dim3(node_blocks + copy_blocks), dim3(LED_NT), 0, s, a);
     return hipGetLastError();
+}
+
+// Work spans for callers that may not allocate (code under graph capture, serving loops
+// that forbid hipMalloc): one array per GPU, held from the first use until the process
+// ends.  Host code never uses the array's name as an address: the device address is
+// asked for once per device and kept.
+constexpr size_t LEDGER_SCRATCH_BYTES = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[LEDGER_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+unsigned char* g_scratch_ptr[MAX_DEVICES];     // device address of `scratch` on each GPU, null = not asked yet
+}  // namespace
+
+size_t gd_ledger_static_bytes() { return LEDGER_SCRATCH_BYTES; }
+
+hipError_t gd_launch_ledger_static(gd_ledger_args a, hipStream_t s, bool* fits) {
+    *fits = true;
+    if (a.T == 0) return hipSuccess;
+    const size_t NW = ((size_t)a.N + 63) / 64;
+    const size_t rise_bytes = ((size_t)a.T * NW * 8 + 255) & ~(size_t)255;
+    if (rise_bytes + a.lay.counts_bytes > LEDGER_SCRATCH_BYTES) { *fits = false; return hipSuccess; }
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+    }
+    // Nothing in either span has to start at zero: the counting kernel writes every
+    // (node word, step) of the map and every staged count before the finishing kernel,
+    // behind it on the stream, reads them.
+    a.rise = reinterpret_cast<uint64_t*>(g_scratch_ptr[dev]);
+    a.counts_new = g_scratch_ptr[dev] + rise_bytes;
+    return gd_launch_ledger(a, s);
 }
 
 hipError_t gd_launch_ledger_flags(const gd_ledger_flags_args& a, hipStream_t s) {

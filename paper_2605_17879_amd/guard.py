@@ -25,7 +25,8 @@ EXPORTS = ("gd_default_config", "gd_create", "gd_destroy", "gd_state_bytes", "gd
            "gd_set_streaming_steps", "gd_score_batch", "gd_update_window", "gd_flags",
            "gd_topk_nodes", "gd_severity", "gd_sweep_score", "gd_probe_read", "gd_last_error",
            "gd_default_ledger_config", "gd_ledger_bytes", "gd_bind_ledger", "gd_update_ledger",
-           "gd_ledger_flags", "gd_topk_nodes_mean", "gd_set_streaming_hints", "gd_apply_membership")
+           "gd_ledger_flags", "gd_topk_nodes_mean", "gd_set_streaming_hints", "gd_apply_membership",
+           "gd_update_ledger_static", "gd_ledger_static_scratch_bytes")
 
 
 class GuardError(RuntimeError):
@@ -103,6 +104,10 @@ def load_library() -> ctypes.CDLL:
     lib.gd_bind_ledger.restype = ctypes.c_int
     lib.gd_update_ledger.argtypes = [vp, vp, vp, vp, u32, u64, vp]
     lib.gd_update_ledger.restype = ctypes.c_int
+    lib.gd_update_ledger_static.argtypes = [vp, vp, vp, vp, u32, u64, vp]
+    lib.gd_update_ledger_static.restype = ctypes.c_int
+    lib.gd_ledger_static_scratch_bytes.argtypes = []
+    lib.gd_ledger_static_scratch_bytes.restype = ctypes.c_size_t
     lib.gd_ledger_flags.argtypes = [vp] * 11
     lib.gd_ledger_flags.restype = ctypes.c_int
     lib.gd_topk_nodes_mean.argtypes = [vp, u32, vp, vp, vp]
@@ -338,6 +343,16 @@ class Detector:
         self._check(self.lib.gd_update_ledger(self.h, _p(out["exceed_mask"]), _p(out["node_mask"]),
                                               _p(out["node_z"]), T, first, self._stream(stream)))
         self.ledger_steps_seen = first + T
+
+    def update_ledger_static(self, out: dict, T: int, first_step_index: Optional[int] = None, stream=None):
+        """gd_update_ledger with the library's static work area (the call allocates nothing)."""
+        first = self.ledger_steps_seen if first_step_index is None else first_step_index
+        self._check(self.lib.gd_update_ledger_static(self.h, _p(out["exceed_mask"]), _p(out["node_mask"]),
+                                                     _p(out["node_z"]), T, first, self._stream(stream)))
+        self.ledger_steps_seen = first + T
+
+    def ledger_static_scratch_bytes(self) -> int:
+        return int(self.lib.gd_ledger_static_scratch_bytes())
 
     def alloc_ledger_flags(self) -> dict:
         torch, d = self._torch, self.device
