@@ -235,7 +235,10 @@ def test_ledger_at_the_benchmark_size():
     det = detector_for(p)
     det.alloc_ledger(T, recur_horizon=3000, recur_limit=3)
     feed(det, exceed, node_mask, node_z, [T])
-    compare_ledger(want, read_ledger(det, 64), "benchmark size", ranks=ranks, nodes=nodes)
+    compare_ledger(want, read_ledger(det, 64),
+                   f"benchmark size (per-indicator outputs on {len(ranks)} sampled ranks and {len(nodes)} sampled "
+                   "nodes -- items are independent of each other; everything else on all nodes)",
+                   ranks=ranks, nodes=nodes)
     say("  sampled ranks ever flagged", int((want["ranks"].first >= 0).sum()), "episodes",
         np.bincount(want["episodes"]).tolist(), "terminal nodes", int((want["terminal"] >= 0).sum()))
     assert (want["terminal"] >= 0).any() and (want["ranks"].first >= 0).any()
