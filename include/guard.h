@@ -35,8 +35,8 @@
  *   - Arguments are validated on the host before anything is launched; a call
  *     that returns an error has launched nothing.  No exception crosses the ABI.
  *   - A NaN in the telemetry is a sample that did not arrive (see gd_score_batch).
- *     An infinity is tolerated (no fault, no out-of-bounds access) but that
- *     column's results are unspecified.
+ *     Infinities are unsupported input: the results of a column that holds one
+ *     are unspecified.
  *   - A handle is not thread safe.  gd_score_batch is stateless; only
  *     gd_update_window writes the bound state; gd_flags / gd_topk_nodes /
  *     gd_severity read it; only gd_update_ledger writes the bound ledger.
@@ -116,6 +116,8 @@ gd_status gd_bind_state(gd_handle h, void* d_state, size_t state_bytes);
 gd_status gd_set_streaming_steps(gd_handle h, uint32_t max_steps);
 
 /*
+ * (A tuning call, like the one above: no part of the paper's method and without
+ * influence on any result.)
  * Where one-step calls of gd_score_batch may start looking: d_med and d_mad are device
  * arrays [n_metrics] holding the medians and MADs of a recent step -- normally the
  * previous call's own d_med and d_mad outputs, which may be the very buffers the next
@@ -156,7 +158,7 @@ gd_status gd_set_streaming_hints(gd_handle h, const float* d_med, const float* d
  * MAD, which are taken over the samples present (the middle one of an odd number);
  * its z is 0, it never exceeds and it adds 0 to its node's score.  A column with
  * no sample present reports med = MAD = NaN and no exceedance.  Infinities remain
- * unsupported input (no fault; that column's results are unspecified).
+ * unsupported input (that column's results are unspecified).
  */
 gd_status gd_score_batch(gd_handle h, const float* d_x, uint32_t T, float* d_med, float* d_mad,
                          float* d_z, uint8_t* d_exceed_mask, uint64_t* d_rank_anom,
@@ -165,7 +167,8 @@ gd_status gd_score_batch(gd_handle h, const float* d_x, uint32_t T, float* d_med
 
 /*
  * Append T evaluations to the persistence windows of the bound state (Section
- * 4.2: "sustained ... across consecutive evaluation windows").  For every rank
+ * 4.2: only a deviation that lasts over successive evaluations counts; k of the
+ * last W is this library's reading, the paper names no window).  For every rank
  * and node, at every appended step t = first_step_index .. first_step_index+T-1:
  * count = anomalous steps among the last W steps ending at t; the item is
  * flagged while count >= persist_k; the first flagged step is remembered.
@@ -182,7 +185,10 @@ gd_status gd_update_window(gd_handle h, const uint64_t* d_rank_anom, const uint6
                            void* stream);
 
 /*
- * Read the current decision out of the state.
+ * Read the current decision out of the state (Section 4.2: a node whose deviation has
+ * lasted is flagged as fail-slow; the paper acts on nodes, Section 7.1, so a node also
+ * reports whether one of its 8 GPUs is flagged).  Flags are instantaneous; the first
+ * flagged step is kept besides (the paper is silent on a flag's lifetime).
  *   d_rank_flag  [R] u8   1 while count >= persist_k
  *   d_rank_count [R] u16  anomalous steps inside the current window
  *   d_rank_first [R] i32  first step at which the rank was flagged, -1 = never
@@ -196,7 +202,8 @@ gd_status gd_flags(gd_handle h, uint8_t* d_rank_flag, uint16_t* d_rank_count,
                    int32_t* d_node_first, void* stream);
 
 /*
- * The k slowest nodes: all N nodes ordered by (window count, high first; latest
+ * The k slowest nodes.  The paper ranks nothing (a flagged node is simply handed to
+ * mitigation, Section 4.2); the order is this library's: all N nodes ordered by (window count, high first; latest
  * primary node score, high first, -0 == +0; node index, low first).
  *   d_idx [k] i32  node indices in that order
  *   d_key [k] u64  count << 48 | order_key(score) << 16 | (0xFFFF - index), where
@@ -206,7 +213,8 @@ gd_status gd_flags(gd_handle h, uint8_t* d_rank_flag, uint16_t* d_rank_count,
 gd_status gd_topk_nodes(gd_handle h, uint32_t k, int32_t* d_idx, uint64_t* d_key, void* stream);
 
 /*
- * Elastic membership: marks the ranks that take no part in a step as missing samples
+ * Elastic membership (the paper is silent on ranks that join or leave a job; this is
+ * the missing-sample rule of gd_score_batch applied to whole ranks): marks the ranks that take no part in a step as missing samples
  * of that step, in place, before gd_score_batch sees the batch.
  *   d_x      in/out [T][M][R] f32 device, 16-byte aligned
  *   d_active in     [T][ceil(R/64)] u64 device: bit r%64 of word r/64 set = rank r takes
@@ -267,8 +275,8 @@ gd_status gd_sweep_score(gd_handle h, const float* d_flops, const float* d_bw, u
 /*
  * The ledger: bookkeeping beyond the default rule, in a buffer of its own.
  *
- *  - Persistence per indicator, the other reading of Section 4.2's "multiple
- *    performance indicators ... sustained across consecutive evaluation windows":
+ *  - Persistence per indicator, the other reading of Section 4.2's rule that several
+ *    indicators must deviate and keep deviating over successive evaluations:
  *    each metric keeps its own count of exceeding steps among the last `window`, a
  *    metric is sustained when that count has reached persist_k, and an item (a rank
  *    or a node) is flagged when the primary metric is sustained and at least
@@ -330,7 +338,7 @@ gd_status gd_update_ledger(gd_handle h, const uint8_t* d_exceed_mask, const uint
  * call on that GPU until the process ends.  The call itself allocates nothing, here or
  * in any library it uses.  The ledger may therefore be bound with max_T = 1; T is
  * limited by the array instead: align256(T * ceil(N/64) * 8) + 16 R + 18 N (rounded up
- * to 256 per term) must not exceed it (T <= 5 800 at 65 536 ranks), else
+ * to 256 per term) must not exceed it (T <= 7 024 at 65 536 ranks), else
  * GD_ERR_INVALID_ARG and nothing is launched.
  * Every call on one GPU, from any handle, shares that GPU's array: calls that could
  * overlap there (different streams, different threads) race; calls on one stream do
@@ -367,7 +375,8 @@ gd_status gd_ledger_flags(gd_handle h, uint8_t* d_rank_pmask, uint8_t* d_rank_pf
 gd_status gd_topk_nodes_mean(gd_handle h, uint32_t k, int32_t* d_idx, uint64_t* d_key, void* stream);
 
 /*
- * Diagnostic for benchmarks: reads the first n_bytes (rounded down to a multiple of
+ * NOT part of the detector's contract -- a diagnostic for benchmarks, exported so that
+ * the benchmark can time it through the same library: reads the first n_bytes (rounded down to a multiple of
  * 256 KiB) of d_x with the scoring kernel's own load pattern and does nothing else,
  * so that its duration next to gd_score_batch's gives the ceiling of a single pass
  * over the data on this chip.  d_x 16-byte aligned device memory; d_sink one u32 of

@@ -36,12 +36,19 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "guard_oracle.cpp")
 _LIB = os.path.join(_HERE, "libguard_oracle.so")
+# GUARD_ORACLE_SANITIZE=1 (set by the sanitizer test for its child process, which also
+# preloads the sanitizer runtime) selects a build with -fsanitize=address,undefined.
+_SANITIZE = os.environ.get("GUARD_ORACLE_SANITIZE", "") == "1"
+if _SANITIZE:
+    _LIB = os.path.join(_HERE, "libguard_oracle_san.so")
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with g++ (no fast-math, no FMA contraction)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["g++", "-std=c++17", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+        opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+               "-fno-omit-frame-pointer"] if _SANITIZE else ["-O2"]
+        cmd = ["g++", "-std=c++17", *opt, "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
                "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC]
         subprocess.run(cmd, check=True)
     return _LIB

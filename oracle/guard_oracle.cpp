@@ -230,7 +230,7 @@ void go_score(const go_config* c, const float* x, uint64_t T, float* med, float*
     }
 }
 
-// Persistence ("sustained over consecutive evaluation windows"): for every
+// Persistence (Section 4.2: a deviation must last over successive evaluations): for every
 // item i (a rank or a node) and every step t of the whole history,
 //   c_i(t) = number of anomalous steps among the last W steps ending at t
 // recomputed by an explicit loop; flag_i(t) = c_i(t) >= k; first_i = first t
@@ -426,8 +426,8 @@ void go_apply_membership(float* x, uint64_t T, uint32_t M, uint32_t R, const uin
                     std::memcpy(&x[(t * M + m) * (uint64_t)R + r], &qnan, 4);
 }
 
-// Persistence kept per indicator (the other reading of "multiple performance
-// indicators ... sustained across consecutive evaluation windows", Section 4.2:
+// Persistence kept per indicator (the other reading of Section 4.2's rule that several
+// indicators must deviate and keep deviating over successive evaluations:
 // each indicator must itself be sustained, and the indicators are combined
 // afterwards).  mask is the full history [T][n] of exceed bytes (bit m = metric m
 // exceeds for that item at that step) from step 0.  For every item and step:

@@ -1,7 +1,7 @@
 // The ledger: bookkeeping beyond the default decision rule.
 //
-//  * Persistence per indicator -- the other reading of "multiple performance
-//    indicators ... sustained across consecutive evaluation windows" (Section 4.2):
+//  * Persistence per indicator -- the other reading of Section 4.2's rule that
+//    several indicators must deviate and keep deviating over successive evaluations:
 //    every metric keeps its own k-of-W count per rank and per node, and the
 //    multi-signal rule (primary among them, at least min_signals) is applied to
 //    the metrics that are themselves sustained.

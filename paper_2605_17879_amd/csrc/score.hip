@@ -552,7 +552,10 @@ __device__ __forceinline__ bool mad_from_histogram(SH& sh, const float (&v)[ROWS
             const uint32_t klo = __float_as_uint(fmaxf(wl0, xlo)), khi = __float_as_uint(fminf(wr1, xhi));
             const uint32_t bl0 = (klo - lo) >> shift, bl1 = (__float_as_uint(fmaxf(wl1, xlo)) - lo) >> shift;
             const uint32_t br0 = (__float_as_uint(fminf(wr0, xhi)) - lo) >> shift, br1 = (khi - lo) >> shift;
-            const uint32_t nl = bl1 - bl0 + 1, nr = br1 - br0 + 1;
+            // (at most NB edges a side whatever the hint and the bounds hold -- infinities, NaN
+            // patterns, a window turned inside out: the loop below stays short, and eval()
+            // checks every bucket index against bmax before it reads a prefix sum)
+            const uint32_t nl = min(bl1 - bl0 + 1, (uint32_t)NB), nr = min(br1 - br0 + 1, (uint32_t)NB);
             for (uint32_t e = tid; e < nl + nr; e += NT) pair_edge(e < nl ? bl0 + e : br0 + (e - nl));
         } else {
 #pragma unroll

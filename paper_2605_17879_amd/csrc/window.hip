@@ -1,6 +1,6 @@
-// Sliding-window persistence (k anomalous evaluations among the last W:
-// "sustained deviation ... across consecutive evaluation windows", Section 4.2)
-// and the read-out of the current flags.
+// Sliding-window persistence (k anomalous evaluations among the last W: the
+// requirement of Section 4.2 that a deviation persists over several evaluations
+// in a row before a node is flagged) and the read-out of the current flags.
 //
 // State in HBM, per item (a rank or a node): a ring of the last W anomaly bits,
 // stored as the scoring kernel's own bit words ring[step % W][item / 64]; a u16
