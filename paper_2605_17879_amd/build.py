@@ -55,8 +55,9 @@ def tiling_of(symbol: str):
 
 
 # Ragged tilings (rank counts that do not fill the register tile: bounds checks on every
-# row) and the one-wave tilings of up to 1 024 ranks (launch-bound) may keep a few
-# registers in scratch memory; the exact-fit tilings of 256 threads and more may not.
+# row), the one-wave tilings of up to 1 024 ranks (launch-bound) and the per-column route
+# of short batches (latency-bound: one column per workgroup) may keep a few registers in
+# scratch memory; the exact-fit batch tilings of 256 threads and more may not.
 RAGGED_SCRATCH_LIMIT = 128     # bytes per lane
 
 
@@ -67,7 +68,7 @@ def check_register_budget(resources: dict) -> list:
         t = tiling_of(name)
         if t is None:
             continue
-        full = bool(t[3]) and t[0] >= 256
+        full = bool(t[3]) and t[0] >= 256 and not t[4]
         if r.get("VGPRs", 0) + r.get("AGPRs", 0) > VGPR_BUDGET:
             bad.append(f"{name}: {r.get('VGPRs')} VGPRs + {r.get('AGPRs')} AGPRs > {VGPR_BUDGET}")
         scratch = r.get("ScratchSize [bytes/lane]", 0)

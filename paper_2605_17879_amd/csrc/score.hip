@@ -55,11 +55,17 @@ __device__ __forceinline__ float float_of_key(uint32_t k) {
 template <int NT, int LOG_NB, int MAX_NODES>
 struct Shared {
     static constexpr int NB = 1 << LOG_NB;
+    // dlo, hist, dhi are one array of 64 + NB + 64 counters for the hinted counting pass
+    // (keys under / inside / over the bracket); the other passes use hist alone.
+    uint32_t dlo[64];
     uint32_t hist[NB];
+    uint32_t dhi[64];
     uint32_t pref[NB + 4];     // exclusive prefix sums of hist (pref[NB] = total), for the MAD shortcut
     uint32_t cand[CAND_CAP + 4];   // 16-byte aligned; read four at a time when ranking
     uint32_t wpart[16];
     uint32_t below, ncand;
+    uint32_t nkept;            // hinted MAD: candidates kept after the exact test
+    uint32_t mres[4];          // hinted MAD: edge indices found by the search, and a found flag
     uint32_t smin, smax;       // extremes of the sample keys
     uint32_t d1, d2;           // MAD shortcut: distance interval holding the wanted ranks
     uint32_t umax[2];          // largest raw bit pattern of the column (double-buffered)
@@ -68,7 +74,9 @@ struct Shared {
     // far below / above it the counting histogram reached (hok = the hint is usable).
     float hmed[8], hwl[8], hwh[8], hmad[8];
     uint32_t hok[8];
+    uint32_t hfast[8];         // the hinted selection below has not failed for this metric yet
     uint8_t nodeb[MAX_NODES];
+    uint64_t ranka[MAX_NODES / 8 > 0 ? MAX_NODES / 8 : 1];     // the step's rank anomaly words (zero between steps)
 };
 
 // Cross-lane moves with immediate patterns (DPP): no address registers, nothing
@@ -623,6 +631,238 @@ __device__ __forceinline__ bool mad_from_histogram(SH& sh, const float (&v)[ROWS
     return true;
 }
 
+// Hinted selection: median and MAD of a sign-free column whose predecessor (the same
+// metric one step earlier) left a bracket [hint_lo, hint_hi] around its median that
+// reaches past median -+ MAD, and its MAD.  Three passes over the registers instead of
+// the four of the general route, each with less work per value:
+//   1. counting: every key adds one to a counter -- its bucket inside the bracket, or a
+//      lane-private word under / over it (no test, no branch: the bucket index is clamped);
+//      the pass also finds the largest bit pattern of the column.
+//   2. the median's bucket(s) are gathered and ranked as in the general route.
+//   3. MAD: with the exact median, the threads search the prefix sums for the right edge
+//      e and the left edge f with  #[f, e) <= k0 < #[f', e + 1) -- the wanted distances
+//      end inside the few buckets around those edges.  One pass gathers the values whose
+//      distance lies between the distances of those buckets' edges (a few dozen); the
+//      values strictly between the two bucket ranges are known from the prefix sums, so
+//      nothing is counted per value.  The gathered values are then classified exactly:
+//        inner: all values of the buckets between the ranges, distance <= DI;
+//        outer: all values beyond the ranges, distance >= DO;
+//      a gathered value with distance < DI counts with the inner ones, those in
+//      [DI, DO] are ranked, and the wanted ranks must fall among them -- else the
+//      function reports failure and the caller selects in the general way.
+// found = 2: median and MAD; 1: the median alone (MAD by the general route); 0: neither
+// (the work area is at rest in every case, the column is never modified).  umax is
+// valid in every case.
+struct HintedResult {
+    int found;                  // 2: median and MAD, 1: median alone, 0: neither
+    uint32_t umax;              // largest raw bit pattern of the column
+    uint32_t m0, m1;            // the two middle keys
+    uint32_t q0, q1;            // the two middle distances (bit patterns)
+};
+
+template <int NT, int ROWS, int LOG_NB, typename SH>
+__device__ __forceinline__ HintedResult hinted_select(SH& sh, const float (&v)[ROWS][4], uint32_t hint_lo,
+                                                      uint32_t hint_hi, float mad_hint, uint32_t k0,
+                                                      uint32_t k1, uint32_t* umax_slot) {
+    HintedResult out = {0, 0u, 0u, 0u, 0u, 0u};
+    constexpr int NB = 1 << LOG_NB;
+    constexpr uint32_t KEY_LIMIT = 0x7D000000u;    // beyond it the signed bucket arithmetic could wrap
+    const uint32_t span0 = hint_hi - hint_lo;
+    const int shift = shift_for<LOG_NB>(span0);
+    // the bracket is widened to all NB buckets (less than twice the hint's span; the caller
+    // has checked that this stays below KEY_LIMIT)
+    constexpr uint32_t bmax = (uint32_t)NB - 1u;
+    const uint32_t lo = hint_lo;
+    const uint32_t hi = lo + ((uint32_t)NB << shift) - 1u;
+    uint32_t* const cnt = sh.dlo;                  // 64 + NB + 64 counters
+    // ---- pass 1: count
+    {
+        const uint32_t tid = opaque_v(threadIdx.x), lane = tid & (WAVE - 1);
+        const uint32_t base = opaque_s(lo - (64u << shift));     // key of counter 0 (mod 2^32)
+        const int cl = 63 - (int)lane, ch = 64 + NB + (int)lane;
+        const int sh_s = (int)opaque_s((uint32_t)shift);
+        uint32_t um = 0;
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+            float(&row)[4] = const_cast<float(&)[4]>(v[j]);
+            asm volatile("" : "+v"(row[0]), "+v"(row[1]), "+v"(row[2]), "+v"(row[3]));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int b = (int)(__float_as_uint(row[i]) - base) >> sh_s;
+                int c;          // b clamped to [cl, ch] (cl < ch): the median of the three
+                asm("v_med3_i32 %0, %1, %2, %3" : "=v"(c) : "v"(b), "v"(cl), "v"(ch));
+                atomicAdd(&cnt[c], 1u);
+            }
+            um = max(max(um, __float_as_uint(row[0])), __float_as_uint(row[1]));
+            um = max(max(um, __float_as_uint(row[2])), __float_as_uint(row[3]));
+            asm volatile("" : "+v"(um));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        um = wave_max_to_last(um);
+        if (lane == WAVE - 1) atomicMax(umax_slot, um);
+    }
+    __syncthreads();
+    const uint32_t tid = opaque_v(threadIdx.x), lane = tid & (WAVE - 1), w = rfl(tid >> 6);
+    const uint32_t umax = rfl(*umax_slot);
+    out.umax = umax;
+    // the lane-private words: everything under the bracket is `below`
+    if (w == 0) {
+        uint32_t d = cnt[lane];
+        cnt[lane] = 0;
+        d = wave_incl_scan(d);
+        if (lane == WAVE - 1) sh.below = d;
+    }
+    if (w == (NT > WAVE ? 1u : 0u)) cnt[64 + NB + lane] = 0;
+    uint32_t below;
+    const bool bracketed = locate<NT, LOG_NB, true, true>(sh, tid, k0, k1, &below);
+    if (umax > KEY_LIMIT || !bracketed || shift < 2) return out;
+    const uint32_t ba = rfl(sh.res[0]), pa = rfl(sh.res[1]);
+    const uint32_t bb = rfl(sh.res[2]), pb = rfl(sh.res[3]);
+    if (pb - pa > (uint32_t)CAND_CAP / 2 || bb - ba > 1u) return out;      // crowded (ties): the general route narrows
+    // ---- pass 2: the median's bucket(s)
+    {
+        const uint32_t clo = lo + (ba << shift);
+        const uint32_t cspan = ((bb - ba + 1u) << shift) - 1u;
+        const uint32_t tok = opaque_s(clo);
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+            uint32_t off[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) off[i] = __float_as_uint(v[j][i]) - tok;
+            if (min(min(off[0], off[1]), min(off[2], off[3])) <= cspan) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (off[i] <= cspan) {
+                        uint32_t pos = atomicAdd(&sh.ncand, 1u);
+                        if (pos < (uint32_t)CAND_CAP) sh.cand[pos] = off[i] + tok;
+                    }
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    __syncthreads();
+    {
+        const uint32_t ncnt = min(sh.ncand, (uint32_t)CAND_CAP);
+        rank_candidates<NT>(sh, tid, ncnt, k0 - below - pa, k1 - below - pa);
+        if (tid == 0) sh.ncand = 0;
+    }
+    const uint32_t s0 = rfl(sh.res[4]), s1 = rfl(sh.res[5]);
+    out.m0 = s0; out.m1 = s1;
+    out.found = 1;
+    const float med = 0.5f * (__uint_as_float(s0) + __uint_as_float(s1));
+    if (!(mad_hint > 0.0f)) return out;
+    // ---- MAD: search the prefix sums.  Candidate c is the right edge e_c (a bucket's lower
+    // edge, e_c > bb); its distance from the median mirrored to the left gives the edge
+    // f_c, the first one above the mirror point.  F_c = #[f_c, e_c) never decreases with c;
+    // the thread that sees F_c <= k0 < F_{c+1} reports e_c, f_c, f_{c+1}.
+    auto edge = [&](uint32_t e) { return __uint_as_float(lo + (e << shift)); };
+    struct Inner { uint32_t count, f; };                 // count ~0u: not a candidate
+    auto inner_count = [&](uint32_t e) -> Inner {
+        if (e <= bb || e > bmax + 1u) return Inner{0xFFFFFFFFu, 0u};
+        const float d = edge(e) - med;
+        const uint32_t kl = __float_as_uint(med - d);
+        if (!(d > 0.0f) || kl < lo || kl > hi) return Inner{0xFFFFFFFFu, 0u};
+        const uint32_t f = ((kl - lo) >> shift) + 1u;
+        return Inner{f <= e ? sh.pref[e] - sh.pref[f] : 0xFFFFFFFFu, f};
+    };
+    {
+        const uint32_t kr = __float_as_uint(med + mad_hint);
+        const uint32_t eh = kr >= lo && kr <= hi ? (kr - lo) >> shift : bmax;   // the edge the hint points at
+        constexpr int CPT = NT >= 512 ? 1 : 512 / NT;          // candidates per thread: at least 512 in all
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) {
+            const uint32_t e = eh - (uint32_t)(NT * CPT / 2) + tid * CPT + c;     // (wraps below 0: rejected as > bmax + 1)
+            const Inner A = inner_count(e), B = inner_count(e + 1u);
+            if (A.count != 0xFFFFFFFFu && B.count != 0xFFFFFFFFu && A.count <= k0 && B.count > k0) {
+                sh.mres[0] = e; sh.mres[1] = A.f; sh.mres[2] = B.f; sh.mres[3] = 1;
+            }
+        }
+    }
+    __syncthreads();
+    const uint32_t found = rfl(sh.mres[3]);
+    const uint32_t e_star = rfl(sh.mres[0]), f_star = rfl(sh.mres[1]), f_next = rfl(sh.mres[2]);
+    __syncthreads();                     // everyone has read the result
+    if (tid == 0) sh.mres[3] = 0;
+    if (!found) return out;
+    // bucket ranges around the edges (one bucket of margin each side)
+    const uint32_t Rb0 = e_star - 1u, Rb1 = min(e_star + 1u, bmax);
+    const uint32_t Lb1 = f_star, Lb0 = f_next >= 2u ? f_next - 2u : 0u;
+    if (Rb0 <= bb || Lb1 >= ba || Lb0 > Lb1) return out;          // ranges reach the median's buckets: general route
+    const float dLi = med - edge(Lb1 + 1u), dLo = med - edge(Lb0);
+    const float dRi = edge(Rb0) - med, dRo = edge(Rb1 + 1u) - med;
+    const float DI = fmaxf(dLi, dRi), DO = fminf(dLo, dRo);
+    const float Da = fminf(dLi, dRi), Db = fmaxf(dLo, dRo);
+    const uint32_t n_in = rfl(sh.pref[Rb0] - sh.pref[Lb1 + 1u]);
+    if (!(Da > 0.0f) || !(DO >= DI)) return out;
+    // ---- pass 3: gather the values whose distance from the median lies in [Da, Db]
+    {
+        const float tokm = __uint_as_float(opaque_s(__float_as_uint(med)));
+        const float toka = __uint_as_float(opaque_s(__float_as_uint(Da)));
+        const uint32_t wspan = __float_as_uint(Db - Da);
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+            uint32_t off[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) off[i] = __float_as_uint(fabsf(v[j][i] - tokm) - toka);   // negative: a large pattern
+            if (min(min(off[0], off[1]), min(off[2], off[3])) <= wspan) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (off[i] <= wspan) {
+                        uint32_t pos = atomicAdd(&sh.ncand, 1u);
+                        if (pos < (uint32_t)CAND_CAP) sh.cand[pos] = __float_as_uint(v[j][i]);
+                    }
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    __syncthreads();
+    const uint32_t g = rfl(sh.ncand);
+    // classify the gathered values exactly (at most CAND_CAP of them)
+    uint32_t keepd[(CAND_CAP + NT - 1) / NT];
+    uint32_t nlt = 0;
+    if (g <= (uint32_t)CAND_CAP) {
+#pragma unroll
+        for (int q = 0; q < (CAND_CAP + NT - 1) / NT; ++q) {
+            keepd[q] = 0xFFFFFFFFu;
+            const uint32_t j = tid + q * NT;
+            if (j < g) {
+                const uint32_t x = sh.cand[j];
+                const uint32_t b = (x - lo) >> shift;          // (values outside the bracket: b is huge)
+                const bool in_l = x >= lo && b >= Lb0 && b <= Lb1, in_r = x >= lo && b >= Rb0 && b <= Rb1;
+                const float d = fabsf(__uint_as_float(x) - med);
+                if (in_l || in_r) {
+                    if (d < DI) nlt += 1u;
+                    else if (d <= DO) keepd[q] = __float_as_uint(d);
+                }
+            }
+        }
+    }
+    __syncthreads();                     // every gathered value has been read: the list is reused
+    if (g <= (uint32_t)CAND_CAP) {
+#pragma unroll
+        for (int q = 0; q < (CAND_CAP + NT - 1) / NT; ++q) {
+            if (keepd[q] != 0xFFFFFFFFu) {
+                const uint32_t pos = atomicAdd(&sh.nkept, 1u);
+                sh.cand[pos] = keepd[q];
+            }
+        }
+        if (nlt) atomicAdd(&sh.below, nlt);
+    }
+    __syncthreads();
+    const uint32_t c_in = n_in + rfl(sh.below), kept = rfl(sh.nkept);
+    const bool ok = g <= (uint32_t)CAND_CAP && c_in <= k0 && k1 < c_in + kept;
+    if (ok) rank_candidates<NT>(sh, tid, kept, k0 - c_in, k1 - c_in);
+    else __syncthreads();
+    if (tid == 0) { sh.ncand = 0; sh.nkept = 0; sh.below = 0; }
+    if (!ok) return out;
+    out.q0 = rfl(sh.res[4]);
+    out.q1 = rfl(sh.res[5]);
+    out.found = 2;
+    return out;
+}
+
 // Signed score and node score of one register row, dividing with the IEEE
 // operator.  AGG 0 = scaled pairwise sum, 1 = max.  This is the route of every
 // column that holds a missing sample.
@@ -693,12 +933,15 @@ __device__ __forceinline__ void score_row_fast(const float (&x)[4], float med, f
 //   * The node score scale*sum(z') is estimated as cc*sum(x) - kk with
 //     cc ~ +-scale/s and kk ~ 8*med*cc.  All roundings of the exact chain and of
 //     the estimate together stay below `margin` (see the caller), so the estimate
-//     decides unless it falls within `margin` of the threshold; then *near is set
-//     for the lane and the caller evaluates the row exactly.
+//     decides unless it falls within `margin` of the threshold.  The estimate is
+//     monotone in sum(x), so the caller hands in a bound sthr on the sum itself,
+//     checked by it against the estimate's own formula: on the far side of sthr the
+//     node cannot exceed nor come near.  *cand is set for the lanes on the near side;
+//     the caller then forms the estimate and, within `margin` of the threshold, the
+//     exact score.
 template <bool LOWER_IS_WORSE>
-__device__ __forceinline__ void score_row_decide(const float (&x)[4], float xstar, float cc, float kk,
-                                                 float thr, float margin, uint32_t* e, float* nz,
-                                                 bool* near) {
+__device__ __forceinline__ void score_row_decide(const float (&x)[4], float xstar, float sthr, uint32_t* e,
+                                                 bool* cand) {
     uint32_t bits = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -708,9 +951,7 @@ __device__ __forceinline__ void score_row_decide(const float (&x)[4], float xsta
     *e = bits;
     const float half = (x[0] + x[1]) + (x[2] + x[3]);
     const float sum = half + lane_xor1(half);
-    const float est = __builtin_fmaf(sum, cc, -kk);
-    *nz = est;
-    *near = fabsf(est - thr) <= margin;
+    *cand = LOWER_IS_WORSE ? sum <= sthr : sum >= sthr;
 }
 
 // FULL: R == NT*4*ROWS exactly, so no lane is padding and no bounds are checked.
@@ -755,11 +996,12 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
 
     uint32_t NE[(ROWS + 3) / 4]; // node mask byte per row, packed
     // the selection's work area starts in its rest state (see the LDS protocol)
-    for (int i = tid; i < SH::NB; i += NT) sh.hist[i] = 0;
+    for (int i = tid; i < SH::NB + 128; i += NT) sh.dlo[i] = 0;      // dlo, hist, dhi
+    for (int i = tid; i < (MAX_NODES / 8 > 0 ? MAX_NODES / 8 : 1); i += NT) sh.ranka[i] = 0;
     if (tid == 0) {
-        sh.umax[0] = 0; sh.umax[1] = 0; sh.ncand = 0; sh.below = 0;
+        sh.umax[0] = 0; sh.umax[1] = 0; sh.ncand = 0; sh.below = 0; sh.nkept = 0; sh.mres[3] = 0;
         sh.smin = 0xFFFFFFFFu; sh.smax = 0; sh.d1 = 0; sh.d2 = 0xFFFFFFFFu;
-        for (int m = 0; m < 8; ++m) sh.hok[m] = 0;
+        for (int m = 0; m < 8; ++m) { sh.hok[m] = 0; sh.hfast[m] = 1; }
         // A one-step call may be told the medians and MADs of a recent step (usually the
         // previous call's outputs).  They take the place of the hints a run of steps builds
         // up for itself; like those they are only trusted as far as the counting pass
@@ -788,6 +1030,10 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         __syncthreads();
     }
 
+    uint32_t dir_codes = 0;          // direction + 1 of metric i in bits 2i, 2i + 1
+#pragma unroll
+    for (int i = 0; i < 8; ++i) dir_codes |= (uint32_t)(a.dir[i] + 1) << (2 * i);
+    dir_codes = rfl(dir_codes);
     const uint32_t k0_all = R / 2 - 1, k1_all = R / 2;   // the middle ranks when nothing is missing (R is even)
     uint32_t colpar = 0;                          // parity of the column count: which umax slot is in use
 
@@ -841,15 +1087,40 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
             hint_hi = rfl(__float_as_uint(xh));
             hinted = xl >= 0.0f && xh > xl && hint_hi < 0x7F800000u;
         }
+        uint32_t* const umax_slot = &sh.umax[colpar];
+        uint32_t umax = 0;
+        uint32_t s0 = 0, s1 = 0;
+        float med = 0.0f;
+        bool have_mad = false;
+        // The hinted selection (sign-free column, exact-fit tiling, a predecessor's bracket and
+        // MAD): median and MAD in three light passes.  Whatever it does not settle goes
+        // through the general route below.
+        int hsel = 0;
+        bool tried_fast = false;
+        if (FULL && hinted && rfl(sh.hfast[m]) != 0 && hint_hi < 0x7D000000u - 2u * (hint_hi - hint_lo) &&
+            hint_hi - hint_lo < 0x20000000u) {
+            tried_fast = true;
+            const HintedResult hr = hinted_select<NT, ROWS, LOG_NB>(sh, v, hint_lo, hint_hi, sh.hmad[m], k0_all,
+                                                                    k1_all, umax_slot);
+            hsel = hr.found;
+            umax = hr.umax;
+            if (hsel == 0) {
+                hinted = false;                 // (and this metric goes the general way from now on)
+                if (tid == 0) sh.hfast[m] = 0;
+            } else {
+                med = 0.5f * (__uint_as_float(hr.m0) + __uint_as_float(hr.m1));
+                have_mad = hsel == 2;
+                s0 = hr.q0; s1 = hr.q1;
+                if (tid == 0) sh.hmed[m] = med;
+            }
+        }
         // Largest raw bit pattern of the column: >= 0x80000000 iff some value carries
         // a sign bit (negative or -0); otherwise it is the bit pattern of the maximum.
         // With a hint the column is taken to be sign-free like its predecessor and the
         // maximum is found by the median's counting pass itself, which starts on the
         // register rows as they arrive; otherwise it takes a pass of its own.
-        const bool fused_umax = FULL && hinted;
-        uint32_t* const umax_slot = &sh.umax[colpar];
-        uint32_t umax = 0;
-        if (__builtin_expect(!fused_umax, 0)) {
+        const bool fused_umax = FULL && hinted && !tried_fast;
+        if (__builtin_expect(!fused_umax && !tried_fast, 0)) {
             uint32_t um = 0;
 #pragma unroll
             for (int j = 0; j < ROWS; ++j) {
@@ -868,10 +1139,7 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         bool special = umax > 0x7F800000u;
         uint32_t k0 = k0_all, k1 = k1_all;
 
-        uint32_t s0 = 0, s1 = 0;
-        float med = 0.0f;
-        bool have_mad = false;
-        if (!special) {
+        if (hsel == 0 && !special) {
             uint32_t hlo = 0, hhi = 0;
             int hshift = 0;
             const bool one_round = block_select<NT, ROWS, LOG_NB, true>(
@@ -947,13 +1215,16 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         if (tid == 0) {
             a.med[t * M + m] = med;
             a.mad[t * M + m] = mad;
+            if (hsel) sh.hmad[m] = mad;         // the hinted selection follows median and MAD step by step
         }
         float s = 1.4826f * mad;
         s = fmaxf(s, a.rel_floor * fabsf(med));
         s = fmaxf(s, a.abs_floor);
 
         // z, exceedance and node scores
-        const int dir = a.dir[m];
+        // (all eight directions in one scalar word: indexing the argument array by m
+        // would be a load from memory, and a wait for it, in every column)
+        const int dir = (int)((dir_codes >> (2u * m)) & 3u) - 1;
         const bool prim = m == a.primary;
         const uint32_t tz = fresh_tid4();
         float* nzrow = a.node_z + t * N;
@@ -1011,7 +1282,7 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         // Decision-only route for supporting one-sided metrics: find the exact boundary
         // xstar of "this rank exceeds" by probing 64 consecutive floats around
         // med +- thr*s with the defining operations (IEEE subtract and divide).
-        bool decide = fast && !prim && dir != 0;
+        bool decide = fast && !prim && dir != 0 && a.node_scale > 0.0f;
         float xstar = 0.0f;
         if (decide) {
             const float xc = dir > 0 ? med + thr * s : med - thr * s;
@@ -1042,6 +1313,18 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         const float kk = (8.0f * med) * cc;
         const float margin = __builtin_fmaf(fabsf(cc) * __uint_as_float(umax), 0x1.01p-16f,
                                             fabsf(thr) * 0x1p-22f);
+        // The bound on sum(x) beyond which the estimate stays under thr - margin: solved
+        // from the estimate's formula with a little slack and then checked with the formula
+        // itself (the estimate rises with the sum when higher is worse, cc > 0, and falls
+        // with it otherwise).  Without a bound that passes the check every row is a candidate.
+        float sthr = dir > 0 ? -__builtin_inff() : __builtin_inff();
+        if (decide) {
+            const float tl = (thr - margin) - fabsf(thr) * 0x1p-20f;
+            const float s0 = (tl + kk) / cc;
+            const float slack = fabsf(s0) * 0x1p-18f + 0x1p-100f;
+            const float sb = dir > 0 ? s0 - slack : s0 + slack;
+            if (__builtin_fmaf(sb, cc, -kk) < tl) sthr = sb;
+        }
         const uint32_t absmask = dir == 0 ? 0x7FFFFFFFu : 0xFFFFFFFFu;
         const uint32_t sgnmask = dir < 0 ? 0x80000000u : 0u;
         // 0/1 decision-only (higher / lower is worse), 2/3 exact by reciprocal
@@ -1054,25 +1337,33 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
             uint32_t e;
             float nz;
             if (rt <= 1u) {
-                bool near;
-                if (rt == 0u) score_row_decide<false>(v[j], xstar, cc, kk, thr, margin, &e, &nz, &near);
-                else score_row_decide<true>(v[j], xstar, cc, kk, thr, margin, &e, &nz, &near);
-                if (__builtin_expect(__ballot(near) != 0, 0)) {       // rare: settle the row with the exact chain
-                    uint32_t e2;
-                    score_row_fast<false>(v[j], med, ss, rs, thr, a.node_scale, &e2, &nz);
+                bool cand;
+                if (rt == 0u) score_row_decide<false>(v[j], xstar, sthr, &e, &cand);
+                else score_row_decide<true>(v[j], xstar, sthr, &e, &cand);
+                nz = thr;                                   // (not above the threshold: no node bit)
+                if (__builtin_expect(__ballot(cand) != 0, 0)) {       // some node may exceed: the estimate decides,
+                    const float half = (v[j][0] + v[j][1]) + (v[j][2] + v[j][3]);     // or, too close, the exact chain
+                    nz = __builtin_fmaf(half + lane_xor1(half), cc, -kk);
+                    if (__builtin_expect(__ballot(fabsf(nz - thr) <= margin) != 0, 0)) {
+                        uint32_t e2;
+                        score_row_fast<false>(v[j], med, ss, rs, thr, a.node_scale, &e2, &nz);
+                    }
+                    NE[j / 4] |= (nz > thr ? 1u : 0u) << (8 * (j & 3) + m);
                 }
-            } else if (rt == 2u) {
-                score_row_fast<false>(v[j], med, ss, rs, thr, a.node_scale, &e, &nz);
-            } else if (rt == 3u) {
-                score_row_fast<true>(v[j], med, ss, rs, thr, a.node_scale, &e, &nz);
-            } else if (__builtin_expect(rt == 4u, 0)) {
-                score_row<0>(v[j], med, s, absmask, sgnmask, thr, a.node_scale, &e, &nz);
             } else {
-                score_row<1>(v[j], med, s, absmask, sgnmask, thr, a.node_scale, &e, &nz);
+                if (rt == 2u) {
+                    score_row_fast<false>(v[j], med, ss, rs, thr, a.node_scale, &e, &nz);
+                } else if (rt == 3u) {
+                    score_row_fast<true>(v[j], med, ss, rs, thr, a.node_scale, &e, &nz);
+                } else if (__builtin_expect(rt == 4u, 0)) {
+                    score_row<0>(v[j], med, s, absmask, sgnmask, thr, a.node_scale, &e, &nz);
+                } else {
+                    score_row<1>(v[j], med, s, absmask, sgnmask, thr, a.node_scale, &e, &nz);
+                }
+                NE[j / 4] |= (nz > thr ? 1u : 0u) << (8 * (j & 3) + m);
             }
             __hip_atomic_fetch_or(&emask[j * NT + tz / 4], e << m, __ATOMIC_RELAXED,
                                   __HIP_MEMORY_SCOPE_WORKGROUP);
-            NE[j / 4] |= (nz > thr ? 1u : 0u) << (8 * (j & 3) + m);
             if (prim && (FULL || rbase(j, tz) < R) && !(tz & 4)) nzrow[rbase(j, tz) / 8] = nz;
             if (!SPLIT) load_row(j, next_col, tz);   // the row is done: refill it with the next column
             // pin the row's results here, or its scores stay live until the loop ends
@@ -1100,36 +1391,55 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         }
         return;
     }
-    // per-rank mask bytes and anomaly bits
-    uint64_t* arow = a.rank_anom + t * RW;
+    // per-rank mask bytes and anomaly bits.  Anomalous ranks are rare: their bits are OR-ed
+    // into the step's bit words in LDS (all zero between steps) only by the waves that
+    // hold one, and the finished words are copied out below.
+    const uint32_t min_signals = rfl(a.min_signals), others_mask = ~(0x01010101u << a.primary);
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
         const bool valid = FULL || rbase(j, to) < R;
         const uint32_t Ej = emask[j * NT + to / 4];
         if (valid) *reinterpret_cast<uint32_t*>(erow + rbase(j, to)) = Ej;
-        // multi-signal rule on the four mask bytes at once: primary bit set and
-        // per-byte popcount >= min_signals (adding 0x80 - min_signals carries into bit 7)
+        // multi-signal rule on the four mask bytes at once: primary bit set and at least
+        // min_signals bits in the byte
         const uint32_t prim_set = (Ej >> a.primary) & 0x01010101u;
-        uint32_t pc = Ej - ((Ej >> 1) & 0x55555555u);
-        pc = (pc & 0x33333333u) + ((pc >> 2) & 0x33333333u);
-        pc = (pc + (pc >> 4)) & 0x0F0F0F0Fu;
-        const uint32_t enough = ((pc + (0x80u - a.min_signals) * 0x01010101u) >> 7) & 0x01010101u;
-        const uint32_t an = valid ? (prim_set & enough) : 0u;
-        const uint32_t nib = (an | (an >> 7) | (an >> 14) | (an >> 21)) & 0xFu;
-        // 16 consecutive lanes hold one 64-bit word
-        const int sub = lane & 15;
-        uint32_t wlo = sub < 8 ? nib << (4 * sub) : 0u;
-        uint32_t whi = sub >= 8 ? nib << (4 * (sub - 8)) : 0u;
-        wlo |= lane_xor<1>(wlo); whi |= lane_xor<1>(whi);
-        wlo |= lane_xor<2>(wlo); whi |= lane_xor<2>(whi);
-        wlo |= lane_xor<4>(wlo); whi |= lane_xor<4>(whi);
-        wlo |= lane_xor<8>(wlo); whi |= lane_xor<8>(whi);
-        if (sub == 0 && valid)
-            arow[rbase(j, to) / 64] = ((uint64_t)whi << 32) | wlo;
+        uint32_t an;
+        if (min_signals <= 2u) {
+            // (two signals: the primary's and any other -- bit 7 of "low seven bits + 0x7F",
+            // or bit 7 itself, says that a byte is not zero)
+            const uint32_t others = Ej & others_mask;
+            const uint32_t some = (((others & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | others) >> 7;
+            an = min_signals <= 1u ? prim_set : (prim_set & some);
+        } else {
+            // per-byte popcount >= min_signals (adding 0x80 - min_signals carries into bit 7)
+            uint32_t pc = Ej - ((Ej >> 1) & 0x55555555u);
+            pc = (pc & 0x33333333u) + ((pc >> 2) & 0x33333333u);
+            pc = (pc + (pc >> 4)) & 0x0F0F0F0Fu;
+            an = prim_set & ((pc + (0x80u - min_signals) * 0x01010101u) >> 7);
+        }
+        if (!valid) an = 0u;
+        if (__builtin_expect(__ballot(an != 0u) != 0ull, 0)) {
+            // the lane's four ranks are bits rbase % 32 .. + 3 of 32-bit word rbase / 32
+            const uint32_t nib = (an | (an >> 7) | (an >> 14) | (an >> 21)) & 0xFu;
+            const uint32_t r0 = rbase(j, to);
+            if (nib) atomicOr(&reinterpret_cast<uint32_t*>(sh.ranka)[r0 >> 5], nib << (r0 & 31u));
+        }
         if (valid && !(to & 4)) sh.nodeb[rbase(j, to) / 8] = (uint8_t)((NE[j / 4] >> (8 * (j & 3))) & 0xFFu);
     }
     __syncthreads();
-    for (uint32_t n = tid; n < N; n += NT) a.node_mask[t * N + n] = sh.nodeb[n];
+    for (uint32_t q = tid; q < RW; q += NT) {       // (one round at most in the exact-fit tilings)
+        a.rank_anom[t * RW + q] = sh.ranka[q];
+        sh.ranka[q] = 0;
+    }
+    if (FULL) {                                 // N == NT * ROWS / 2: a fixed number of rounds
+#pragma unroll
+        for (int q = 0; q < (ROWS + 1) / 2; ++q) {
+            const uint32_t n = opaque_v((uint32_t)tid) + (uint32_t)q * NT;
+            if (ROWS % 2 == 0 || n < N) a.node_mask[t * N + n] = sh.nodeb[n];
+        }
+    } else {
+        for (uint32_t n = tid; n < N; n += NT) a.node_mask[t * N + n] = sh.nodeb[n];
+    }
     for (uint32_t wd = w; wd < NWD; wd += NWAVES) {
         const uint32_t n = wd * 64 + lane;
         bool an = false;
