@@ -62,10 +62,11 @@ struct Shared {
     uint32_t dhi[64];
     uint32_t pref[NB + 4];     // exclusive prefix sums of hist (pref[NB] = total), for the MAD shortcut
     uint32_t cand[CAND_CAP + 4];   // 16-byte aligned; read four at a time when ranking
+    uint32_t cand2[CAND_CAP + 4];  // hinted MAD: the candidates kept after the exact test
     uint32_t wpart[16];
     uint32_t below, ncand;
     uint32_t nkept;            // hinted MAD: candidates kept after the exact test
-    uint32_t mres[4];          // hinted MAD: edge indices found by the search, and a found flag
+    uint32_t mres[2][4];       // hinted MAD: edge indices found by the search and a found flag (two slots, used in turn)
     uint32_t smin, smax;       // extremes of the sample keys
     uint32_t d1, d2;           // MAD shortcut: distance interval holding the wanted ranks
     uint32_t umax[2];          // largest raw bit pattern of the column (double-buffered)
@@ -256,12 +257,13 @@ __device__ __forceinline__ bool locate(SH& sh, uint32_t tid, uint32_t ka, uint32
 // and the wave counts the lanes that answered yes.  Ends with a barrier.
 template <int NT, typename SH>
 __device__ __forceinline__ void rank_candidates(SH& sh, uint32_t tid, uint32_t cnt, uint32_t wa,
-                                                uint32_t wb) {
+                                                uint32_t wb, const uint32_t* list = nullptr) {
+    if (list == nullptr) list = sh.cand;
     const uint32_t lane = tid & (WAVE - 1), w = rfl(tid >> 6);
     if (cnt <= (uint32_t)WAVE) {
         // one LDS read per wave: lane j holds candidate j, candidate i is read from lane i
         // (read whatever the slot holds: the load then does not wait for cnt)
-        const uint32_t cj = sh.cand[lane];
+        const uint32_t cj = list[lane];
         for (uint32_t i = w; i < cnt; i += NT / WAVE) {
             const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)cj, (int)i);
             const uint32_t r = (uint32_t)__popcll(__ballot(lane < cnt && (cj < c || (cj == c && lane < i))));
@@ -272,11 +274,11 @@ __device__ __forceinline__ void rank_candidates(SH& sh, uint32_t tid, uint32_t c
         }
     } else {
         for (uint32_t i = w; i < cnt; i += NT / WAVE) {
-            const uint32_t c = sh.cand[i];
+            const uint32_t c = list[i];
             uint32_t r = 0;                      // wave-uniform: candidates ordered before candidate i
             for (uint32_t j0 = 0; j0 < cnt; j0 += WAVE) {
                 const uint32_t j = j0 + lane;
-                const uint32_t cj = j < cnt ? sh.cand[j] : 0xFFFFFFFFu;
+                const uint32_t cj = j < cnt ? list[j] : 0xFFFFFFFFu;
                 r += (uint32_t)__popcll(__ballot(j < cnt && (cj < c || (cj == c && j < i))));
             }
             if (lane == 0) {
@@ -663,7 +665,7 @@ struct HintedResult {
 template <int NT, int ROWS, int LOG_NB, typename SH>
 __device__ __forceinline__ HintedResult hinted_select(SH& sh, const float (&v)[ROWS][4], uint32_t hint_lo,
                                                       uint32_t hint_hi, float mad_hint, uint32_t k0,
-                                                      uint32_t k1, uint32_t* umax_slot) {
+                                                      uint32_t k1, uint32_t* umax_slot, uint32_t par) {
     HintedResult out = {0, 0u, 0u, 0u, 0u, 0u};
     constexpr int NB = 1 << LOG_NB;
     constexpr uint32_t KEY_LIMIT = 0x7D000000u;    // beyond it the signed bucket arithmetic could wrap
@@ -775,15 +777,14 @@ __device__ __forceinline__ HintedResult hinted_select(SH& sh, const float (&v)[R
             const uint32_t e = eh - (uint32_t)(NT * CPT / 2) + tid * CPT + c;     // (wraps below 0: rejected as > bmax + 1)
             const Inner A = inner_count(e), B = inner_count(e + 1u);
             if (A.count != 0xFFFFFFFFu && B.count != 0xFFFFFFFFu && A.count <= k0 && B.count > k0) {
-                sh.mres[0] = e; sh.mres[1] = A.f; sh.mres[2] = B.f; sh.mres[3] = 1;
+                sh.mres[par][0] = e; sh.mres[par][1] = A.f; sh.mres[par][2] = B.f; sh.mres[par][3] = 1;
             }
         }
     }
     __syncthreads();
-    const uint32_t found = rfl(sh.mres[3]);
-    const uint32_t e_star = rfl(sh.mres[0]), f_star = rfl(sh.mres[1]), f_next = rfl(sh.mres[2]);
-    __syncthreads();                     // everyone has read the result
-    if (tid == 0) sh.mres[3] = 0;
+    // (the caller clears the other slot's flag, which every thread read a column ago)
+    const uint32_t found = rfl(sh.mres[par][3]);
+    const uint32_t e_star = rfl(sh.mres[par][0]), f_star = rfl(sh.mres[par][1]), f_next = rfl(sh.mres[par][2]);
     if (!found) return out;
     // bucket ranges around the edges (one bucket of margin each side)
     const uint32_t Rb0 = e_star - 1u, Rb1 = min(e_star + 1u, bmax);
@@ -819,13 +820,12 @@ __device__ __forceinline__ HintedResult hinted_select(SH& sh, const float (&v)[R
     }
     __syncthreads();
     const uint32_t g = rfl(sh.ncand);
-    // classify the gathered values exactly (at most CAND_CAP of them)
-    uint32_t keepd[(CAND_CAP + NT - 1) / NT];
-    uint32_t nlt = 0;
+    // classify the gathered values exactly (at most CAND_CAP of them); those kept go to a
+    // second list
     if (g <= (uint32_t)CAND_CAP) {
+        uint32_t nlt = 0;
 #pragma unroll
         for (int q = 0; q < (CAND_CAP + NT - 1) / NT; ++q) {
-            keepd[q] = 0xFFFFFFFFu;
             const uint32_t j = tid + q * NT;
             if (j < g) {
                 const uint32_t x = sh.cand[j];
@@ -834,18 +834,8 @@ __device__ __forceinline__ HintedResult hinted_select(SH& sh, const float (&v)[R
                 const float d = fabsf(__uint_as_float(x) - med);
                 if (in_l || in_r) {
                     if (d < DI) nlt += 1u;
-                    else if (d <= DO) keepd[q] = __float_as_uint(d);
+                    else if (d <= DO) sh.cand2[atomicAdd(&sh.nkept, 1u)] = __float_as_uint(d);
                 }
-            }
-        }
-    }
-    __syncthreads();                     // every gathered value has been read: the list is reused
-    if (g <= (uint32_t)CAND_CAP) {
-#pragma unroll
-        for (int q = 0; q < (CAND_CAP + NT - 1) / NT; ++q) {
-            if (keepd[q] != 0xFFFFFFFFu) {
-                const uint32_t pos = atomicAdd(&sh.nkept, 1u);
-                sh.cand[pos] = keepd[q];
             }
         }
         if (nlt) atomicAdd(&sh.below, nlt);
@@ -853,9 +843,12 @@ __device__ __forceinline__ HintedResult hinted_select(SH& sh, const float (&v)[R
     __syncthreads();
     const uint32_t c_in = n_in + rfl(sh.below), kept = rfl(sh.nkept);
     const bool ok = g <= (uint32_t)CAND_CAP && c_in <= k0 && k1 < c_in + kept;
-    if (ok) rank_candidates<NT>(sh, tid, kept, k0 - c_in, k1 - c_in);
+    if (ok) rank_candidates<NT>(sh, tid, kept, k0 - c_in, k1 - c_in, sh.cand2);
     else __syncthreads();
-    if (tid == 0) { sh.ncand = 0; sh.nkept = 0; sh.below = 0; }
+    if (tid == 0) {          // (a zero made here: kept in registers for the whole kernel it ends up spilled)
+        const uint32_t zero = opaque_v(0u);
+        sh.ncand = zero; sh.nkept = zero; sh.below = zero;
+    }
     if (!ok) return out;
     out.q0 = rfl(sh.res[4]);
     out.q1 = rfl(sh.res[5]);
@@ -940,15 +933,19 @@ __device__ __forceinline__ void score_row_fast(const float (&x)[4], float med, f
 //     the caller then forms the estimate and, within `margin` of the threshold, the
 //     exact score.
 template <bool LOWER_IS_WORSE>
-__device__ __forceinline__ void score_row_decide(const float (&x)[4], float xstar, float sthr, uint32_t* e,
-                                                 bool* cand) {
-    uint32_t bits = 0;
+__device__ __forceinline__ void score_row_decide(const float (&x)[4], uint32_t xcut, uint32_t shift_m,
+                                                 uint32_t mask_m, float sthr, uint32_t* e, bool* cand) {
+    // Values and boundary are positive floats, which order like their bit patterns: with
+    // xcut = bits(xstar) - 1 (higher is worse) or bits(xstar) + 1 (lower is worse) the sign of
+    // one integer difference per value is the decision.  The four sign bytes are brought
+    // together by byte permutes and land, shifted, on bit m of the four mask bytes.
+    uint32_t d[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const bool ex = LOWER_IS_WORSE ? x[i] <= xstar : x[i] >= xstar;
-        bits |= (ex ? 1u : 0u) << (8 * i);
-    }
-    *e = bits;
+    for (int i = 0; i < 4; ++i)
+        d[i] = LOWER_IS_WORSE ? __float_as_uint(x[i]) - xcut : xcut - __float_as_uint(x[i]);
+    const uint32_t lo2 = __builtin_amdgcn_perm(d[1], d[0], 0x0C0C0703u);     // bytes: d0.b3, d1.b3, 0, 0
+    const uint32_t hi2 = __builtin_amdgcn_perm(d[3], d[2], 0x07030C0Cu);     // bytes: 0, 0, d2.b3, d3.b3
+    *e = ((lo2 | hi2) >> shift_m) & mask_m;                  // (already in place for metric m)
     const float half = (x[0] + x[1]) + (x[2] + x[3]);
     const float sum = half + lane_xor1(half);
     *cand = LOWER_IS_WORSE ? sum <= sthr : sum >= sthr;
@@ -999,7 +996,7 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
     for (int i = tid; i < SH::NB + 128; i += NT) sh.dlo[i] = 0;      // dlo, hist, dhi
     for (int i = tid; i < (MAX_NODES / 8 > 0 ? MAX_NODES / 8 : 1); i += NT) sh.ranka[i] = 0;
     if (tid == 0) {
-        sh.umax[0] = 0; sh.umax[1] = 0; sh.ncand = 0; sh.below = 0; sh.nkept = 0; sh.mres[3] = 0;
+        sh.umax[0] = 0; sh.umax[1] = 0; sh.ncand = 0; sh.below = 0; sh.nkept = 0; sh.mres[0][3] = 0; sh.mres[1][3] = 0;
         sh.smin = 0xFFFFFFFFu; sh.smax = 0; sh.d1 = 0; sh.d2 = 0xFFFFFFFFu;
         for (int m = 0; m < 8; ++m) { sh.hok[m] = 0; sh.hfast[m] = 1; }
         // A one-step call may be told the medians and MADs of a recent step (usually the
@@ -1030,6 +1027,7 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         __syncthreads();
     }
 
+    const float inv_node_scale = 1.0f / a.node_scale;      // (only used where node_scale > 0)
     uint32_t dir_codes = 0;          // direction + 1 of metric i in bits 2i, 2i + 1
 #pragma unroll
     for (int i = 0; i < 8; ++i) dir_codes |= (uint32_t)(a.dir[i] + 1) << (2 * i);
@@ -1101,7 +1099,7 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
             hint_hi - hint_lo < 0x20000000u) {
             tried_fast = true;
             const HintedResult hr = hinted_select<NT, ROWS, LOG_NB>(sh, v, hint_lo, hint_hi, sh.hmad[m], k0_all,
-                                                                    k1_all, umax_slot);
+                                                                    k1_all, umax_slot, colpar);
             hsel = hr.found;
             umax = hr.umax;
             if (hsel == 0) {
@@ -1171,7 +1169,7 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         }
         }
         // the other slot is free again: every thread read it a column ago
-        if (tid == 0) sh.umax[colpar ^ 1u] = 0;
+        if (tid == 0) { sh.umax[colpar ^ 1u] = 0; sh.mres[colpar ^ 1u][3] = 0; }
         colpar ^= 1u;
         uint32_t present = R;
         if (__builtin_expect(special, 0)) {
@@ -1284,28 +1282,31 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         // med +- thr*s with the defining operations (IEEE subtract and divide).
         bool decide = fast && !prim && dir != 0 && a.node_scale > 0.0f;
         float xstar = 0.0f;
-        if (decide) {
+        // One vector division serves both: lanes 0..62 probe 63 consecutive floats around
+        // med +- thr*s, lane 63 divides 1 by s (the reciprocal every exact route needs).
+        const float ss = dir < 0 ? -s : s;
+        float rs;
+        {
             const float xc = dir > 0 ? med + thr * s : med - thr * s;
             const uint32_t kc = key_of(xc);
-            decide = kc >= 64u && kc <= 0xFF800000u - 64u;
+            decide = decide && kc >= 64u && kc <= 0xFF800000u - 64u;
+            const float xl = float_of_key(kc + (uint32_t)lane - 31u);
+            const float num = lane == WAVE - 1 ? 1.0f : (dir > 0 ? xl - med : med - xl);
+            const float q = num / s;
+            const float r1 = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(q), WAVE - 1));
+            rs = dir < 0 ? -r1 : r1;                         // 1/(-s) = -(1/s) exactly
             if (decide) {
-                const float xl = float_of_key(kc + (uint32_t)lane - 32u);
-                const float zl = dir > 0 ? (xl - med) / s : (med - xl) / s;
-                const uint64_t mk = __ballot(zl > thr);
-                // higher is worse: lanes f..63 true; lower is worse: lanes 0..g-1 true
-                const uint64_t want = dir > 0 ? mk : ~mk;
+                const uint64_t probes = ~(1ull << (WAVE - 1));
+                const uint64_t mk = __ballot(q > thr) & probes;
+                // higher is worse: lanes f..62 true; lower is worse: lanes 0..f-1 true
+                const uint64_t want = dir > 0 ? mk : ~mk & probes;
                 const int f = want ? __builtin_ctzll(want) : 64;
-                decide = f >= 1 && f <= 63 && want == (~0ull << f);
+                decide = f >= 1 && f <= 62 && want == ((~0ull << f) & probes);
                 if (decide) xstar = __uint_as_float((uint32_t)__builtin_amdgcn_readlane(
                                 (int)__float_as_uint(xl), dir > 0 ? f : f - 1));
+                decide = decide && xstar > 0.0f;             // (the bit-pattern comparison needs a positive boundary)
             }
         }
-        // One loop over the register rows; the route is the same for the whole column,
-        // but it is chosen per row from an optimiser-opaque copy so that the loop is
-        // not split into one copy per route (each copy would refill the registers on
-        // its own and the column would end up held twice).
-        const float ss = dir < 0 ? -s : s;
-        const float rs = 1.0f / ss;
         // decision-only route:
         // |estimate - exact node score| < |cc| * (sum(x) + 8*med) * 2^-20 + |thr| * 2^-23
         // and sum(x) + 8*med <= 16 * max(x):
@@ -1314,17 +1315,20 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         const float margin = __builtin_fmaf(fabsf(cc) * __uint_as_float(umax), 0x1.01p-16f,
                                             fabsf(thr) * 0x1p-22f);
         // The bound on sum(x) beyond which the estimate stays under thr - margin: solved
-        // from the estimate's formula with a little slack and then checked with the formula
-        // itself (the estimate rises with the sum when higher is worse, cc > 0, and falls
-        // with it otherwise).  Without a bound that passes the check every row is a candidate.
+        // from the estimate's formula (1/cc = ss / node_scale, closely enough) with a little
+        // slack and then checked with the formula itself (the estimate rises with the sum when
+        // higher is worse, cc > 0, and falls with it otherwise).  Without a bound that passes
+        // the check every row is a candidate.
         float sthr = dir > 0 ? -__builtin_inff() : __builtin_inff();
         if (decide) {
             const float tl = (thr - margin) - fabsf(thr) * 0x1p-20f;
-            const float s0 = (tl + kk) / cc;
+            const float s0 = (tl + kk) * (ss * inv_node_scale);
             const float slack = fabsf(s0) * 0x1p-18f + 0x1p-100f;
             const float sb = dir > 0 ? s0 - slack : s0 + slack;
             if (__builtin_fmaf(sb, cc, -kk) < tl) sthr = sb;
         }
+        const uint32_t xcut = dir > 0 ? __float_as_uint(xstar) - 1u : __float_as_uint(xstar) + 1u;
+        const uint32_t shift_m = 7u - m, mask_m = 0x01010101u << m;
         const uint32_t absmask = dir == 0 ? 0x7FFFFFFFu : 0xFFFFFFFFu;
         const uint32_t sgnmask = dir < 0 ? 0x80000000u : 0u;
         // 0/1 decision-only (higher / lower is worse), 2/3 exact by reciprocal
@@ -1334,12 +1338,13 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
 #pragma unroll
         for (int j = 0; j < ROWS; ++j) {
             const uint32_t rt = opaque_s(route);
-            uint32_t e;
+            uint32_t e, eplaced;
             float nz;
             if (rt <= 1u) {
                 bool cand;
-                if (rt == 0u) score_row_decide<false>(v[j], xstar, sthr, &e, &cand);
-                else score_row_decide<true>(v[j], xstar, sthr, &e, &cand);
+                if (rt == 0u) score_row_decide<false>(v[j], xcut, shift_m, mask_m, sthr, &e, &cand);
+                else score_row_decide<true>(v[j], xcut, shift_m, mask_m, sthr, &e, &cand);
+                eplaced = e;                                // (its bits are on metric m already)
                 nz = thr;                                   // (not above the threshold: no node bit)
                 if (__builtin_expect(__ballot(cand) != 0, 0)) {       // some node may exceed: the estimate decides,
                     const float half = (v[j][0] + v[j][1]) + (v[j][2] + v[j][3]);     // or, too close, the exact chain
@@ -1361,8 +1366,9 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
                     score_row<1>(v[j], med, s, absmask, sgnmask, thr, a.node_scale, &e, &nz);
                 }
                 NE[j / 4] |= (nz > thr ? 1u : 0u) << (8 * (j & 3) + m);
+                eplaced = e << m;
             }
-            __hip_atomic_fetch_or(&emask[j * NT + tz / 4], e << m, __ATOMIC_RELAXED,
+            __hip_atomic_fetch_or(&emask[j * NT + tz / 4], eplaced, __ATOMIC_RELAXED,
                                   __HIP_MEMORY_SCOPE_WORKGROUP);
             if (prim && (FULL || rbase(j, tz) < R) && !(tz & 4)) nzrow[rbase(j, tz) / 8] = nz;
             if (!SPLIT) load_row(j, next_col, tz);   // the row is done: refill it with the next column
