@@ -1040,7 +1040,12 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
     // lies above every real key).
     auto load_row = [&](int j, const float* col, uint32_t tid4) {
         float4 q;
-        if (FULL || rbase(j, tid4) < R) {
+        if (FULL) {
+            // (a uniform row pointer plus the lane's 32-bit offset: one address mode, no vector
+            // arithmetic per row)
+            const float* rowp = col + (uint32_t)((j + w) & (ROWS - 1)) * BLK;
+            q = *reinterpret_cast<const float4*>(rowp + tid4);
+        } else if (rbase(j, tid4) < R) {
             q = *reinterpret_cast<const float4*>(col + rbase(j, tid4));
         } else {
             const float pad = __uint_as_float(0x7FFFFFFFu);
@@ -1335,6 +1340,7 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         // (one- / two-sided), 4/5 IEEE division (scaled sum / max)
         const uint32_t route = fast ? (decide ? (dir > 0 ? 0u : 1u) : (dir != 0 ? 2u : 3u))
                                     : (a.node_agg == 0 ? 4u : 5u);
+        uint32_t* const emask_lane = emask + opaque_v((uint32_t)tid);      // (row j: a constant offset from here)
 #pragma unroll
         for (int j = 0; j < ROWS; ++j) {
             const uint32_t rt = opaque_s(route);
@@ -1368,8 +1374,7 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
                 NE[j / 4] |= (nz > thr ? 1u : 0u) << (8 * (j & 3) + m);
                 eplaced = e << m;
             }
-            __hip_atomic_fetch_or(&emask[j * NT + tz / 4], eplaced, __ATOMIC_RELAXED,
-                                  __HIP_MEMORY_SCOPE_WORKGROUP);
+            __hip_atomic_fetch_or(&emask_lane[j * NT], eplaced, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             if (prim && (FULL || rbase(j, tz) < R) && !(tz & 4)) nzrow[rbase(j, tz) / 8] = nz;
             if (!SPLIT) load_row(j, next_col, tz);   // the row is done: refill it with the next column
             // pin the row's results here, or its scores stay live until the loop ends
