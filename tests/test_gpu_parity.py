@@ -850,3 +850,63 @@ def _regime_case(R, T, seed):
     rep = compare_scores(o, out, "regime changes")
     say("  report", rep)
     det.close()
+
+
+HINTED_KINDS = ["binade", "huge", "integers", "tied_centre", "denormal", "ramp", "one_sided", "bimodal",
+                "narrowing"]
+
+
+@pytest.mark.parametrize("R", [1024, 4096, 65536])
+@pytest.mark.parametrize("kind", HINTED_KINDS)
+def test_hinted_selection_on_stationary_runs_of_awkward_columns(kind, R):
+    """Several consecutive steps of the same kind of column in exact-fit tilings, so that from
+    the second step on the hinted selection runs (bracket, median and MAD carried over): columns
+    centred on a power of two, magnitudes beyond its key limit, integer sensors, a third of the
+    ranks tied at the centre, denormals, sorted ranks (every candidate in one wave), one-sided
+    and bimodal distributions (the two distance ranges far from symmetric, or falling into a
+    gap), and a spread that shrinks a hundredfold from one step to the next."""
+    # (a batch is dealt out in runs of ceil(T / workgroups) consecutive steps: three steps per run here)
+    T, M = {1024: 12300, 4096: 3080, 65536: 772}[R], 3
+    say(f"case hinted selection kind={kind} R={R} T={T}")
+    g = torch.Generator().manual_seed(len(kind) * 1000 + R)
+    n = torch.randn((T, M, R), generator=g, dtype=torch.float32).to(torch.float64)
+    u = torch.rand((T, M, R), generator=g, dtype=torch.float32).to(torch.float64).clamp_(1e-7, 1.0)
+    if kind == "binade":
+        centre = torch.tensor([1.0, 2.0, 0.5], dtype=torch.float64)[None, :, None]
+        x = centre * (1.0 + 3e-4 * n)
+    elif kind == "huge":
+        x = 1.5e38 * torch.exp(0.02 * n)
+        x[:, 1] = 2e37 * torch.exp(0.3 * n[:, 1])
+    elif kind == "integers":
+        x = torch.round(65.0 + 2.0 * n)
+        x[:, 2] = torch.round(1000.0 + 40.0 * n[:, 2])
+    elif kind == "tied_centre":
+        x = torch.exp(0.02 * n)
+        x = torch.where(u < 0.33, torch.ones_like(x), x)
+    elif kind == "denormal":
+        x = 3e-41 * torch.exp(0.1 * n)
+        x[:, 1] = 1.2e-38 * (1.0 + 0.01 * n[:, 1])         # straddles the smallest normal number
+    elif kind == "ramp":
+        x = (1.0 + torch.arange(R, dtype=torch.float64) / R)[None, None, :] * (1.0 + 1e-3 * n[:, :, :1])
+        x[:, 1] = torch.flip(x[:, 1], dims=[-1])
+    elif kind == "one_sided":
+        x = 1.0 - torch.log(u) * 0.05                        # exponential tail to the right only
+        x[:, 2] = 400.0 + torch.log(u[:, 2]) * 7.0           # ... and to the left only
+    elif kind == "bimodal":
+        x = torch.where(u < 0.5, 1.0 + 0.001 * n, 1.3 + 0.001 * n)
+        x[:, 1] = torch.where(u[:, 1] < 0.26, 0.8 + 0.01 * n[:, 1], 1.0 + 0.0005 * n[:, 1])
+    elif kind == "narrowing":
+        spread = torch.tensor([0.05 * 0.01 ** (t % 3) for t in range(T)], dtype=torch.float64)[:, None, None]
+        x = 1.0 + spread * n
+    x = x.to(torch.float32)
+    x[:, :, 8:16] *= 1.2 if kind != "huge" else 1.0           # one slow node
+    dirs = (1, -1, 1)
+    p = oracle_params(R=R, M=M, W=4, k=2, directions=dirs)
+    import gpu_harness
+    gpu_harness.STREAMING_STEPS = 0                             # whole-run route: hints carried from step to step
+    try:
+        rep = run_and_compare(p, x, topk_k=min(8, R // 8), chunks=[T], label=f"{kind}-R{R}")
+    finally:
+        gpu_harness.STREAMING_STEPS = None
+    say("  report", rep)
+    assert rep["z_bit_exact"]
