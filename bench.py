@@ -21,7 +21,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0
 
@@ -34,35 +33,48 @@ def algorithmic_bytes_per_launch(R: int, M: int, T: int) -> int:
     return per_step * T
 
 
-def measured_traffic():
-    """HBM bytes per scoring launch from the committed counter runs, or None when
-    the kernel source has changed since they were taken."""
+def _score_source_hash() -> str:
     import hashlib
-    path = os.path.join(ROOT, "profiles", "score_kernel_c3_traffic.json")
     src = os.path.join(ROOT, "paper_2605_17879_amd", "csrc", "score.hip")
+    return hashlib.sha256(open(src, "rb").read()).hexdigest()
+
+
+def _profile_record(name: str):
+    """A committed counter record under profiles/, or None when the kernel source has
+    changed since it was taken (the figures would no longer describe this kernel)."""
     try:
-        rec = json.load(open(path))
-        sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
-        if rec.get("score_hip_sha256") == sha:
-            return rec["hbm_bytes_per_launch"]
+        rec = json.load(open(os.path.join(ROOT, "profiles", name)))
+        if rec.get("score_hip_sha256") == _score_source_hash():
+            return rec
     except (OSError, ValueError, KeyError):
         pass
     return None
 
 
-VALU_PER_SAMPLE = 28.5      # SQ_INSTS_VALU x 64 / samples, profiles/score_kernel_c3_counters.txt
-SIMDS, CLOCK_HZ = 1024, 2.4e9
+def measured_traffic():
+    """HBM bytes per scoring launch from the committed counter runs, or None."""
+    rec = _profile_record("score_kernel_c3_traffic.json")
+    return rec["hbm_bytes_per_launch"] if rec else None
 
 
-def issue_view(samples: int, score_ms: float) -> dict:
-    """Why the HBM fraction is what it is: the share of all SIMD cycles of the chip
-    (256 CUs x 4 SIMDs at 2.4 GHz, one 64-lane vector instruction per 4 cycles) that the
-    scoring launch spends issuing vector instructions, from the profiled instruction
-    count per sample and this run's launch time."""
-    cycles = VALU_PER_SAMPLE * samples / 64 * 4
-    return {"valu_instructions_per_sample": VALU_PER_SAMPLE,
-            "simd_cycles_issuing_valu": cycles / (score_ms * 1e-3 * CLOCK_HZ * SIMDS),
-            "what": "instruction count from rocprofv3 counters (profiles/), time from this run"}
+def issue_view(torch, samples: int, score_ms: float) -> dict:
+    """Why the HBM fraction is what it is: the share of all SIMD cycles of the chip (compute
+    units x 4 SIMDs at the device's clock, one 64-lane vector instruction per 4 cycles)
+    that the scoring launch spends issuing vector instructions -- instruction count per
+    sample from the committed counter profile (null once the kernel has changed since),
+    time from this run."""
+    rec = _profile_record("score_kernel_c3_counters.json")
+    prop = torch.cuda.get_device_properties(0)
+    clock_hz = float(getattr(prop, "clock_rate", 2400000)) * 1e3       # kHz
+    simds = prop.multi_processor_count * 4
+    out = {"valu_instructions_per_sample": None, "simd_cycles_issuing_valu": None,
+           "clock_hz": clock_hz, "simds": simds,
+           "what": "instruction count from rocprofv3 counters (profiles/score_kernel_c3_counters.json), time from this run"}
+    if rec:
+        vps = rec["valu_instructions_per_sample"]
+        out["valu_instructions_per_sample"] = vps
+        out["simd_cycles_issuing_valu"] = vps * samples / 64 * 4 / (score_ms * 1e-3 * clock_hz * simds)
+    return out
 
 
 def make_detector(w):
@@ -75,9 +87,9 @@ def make_detector(w):
 def cpu_baseline(w, x_dev, sample_steps: int) -> dict:
     """The oracle, as it stands, on the first `sample_steps` steps of the same tensor."""
     import oracle
-    from gpu_harness import oracle_params
     xs = x_dev[:sample_steps].cpu().numpy()
-    p = oracle_params(w)
+    p = oracle.Params(R=w.R, M=w.M, W=w.W, k=w.k, thr=w.thr, directions=tuple(w.directions),
+                      primary=w.primary, min_signals=w.min_signals)
     t0 = time.perf_counter()
     oracle.detect(p, xs, topk_k=w.topk, want_z=False)
     dt = time.perf_counter() - t0
@@ -163,6 +175,34 @@ def z_variant(torch, det, w, x, stream, alg_bytes: int) -> dict:
             "GB/s": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
 
+def c2_leg(torch, stream) -> dict:
+    """The 16 384-rank configuration (16 384 ranks x 10 000 steps x 4 metrics, another register
+    tiling of the same kernel) in one gd_score_batch call: launch time by HIP events on the
+    launch stream, algorithmic bytes, fraction of the HBM peak.  Not part of `value`."""
+    from workloads import generate, workload
+    w = workload(2)
+    x = generate(w, seed=2, device="cuda")
+    det = make_detector(w)
+    out = det.alloc_outputs(w.T)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(7)]
+    with torch.cuda.stream(stream):
+        for s0, s1 in ev:
+            s0.record(stream)
+            det.score_batch(x, out, stream)
+            s1.record(stream)
+        torch.cuda.synchronize()
+    ms = sorted(s0.elapsed_time(s1) for s0, s1 in ev[2:])
+    avg = sum(ms) / len(ms)
+    alg = algorithmic_bytes_per_launch(w.R, w.M, w.T)
+    det.close()
+    del x, out
+    return {"workload": f"{w.R} ranks x {w.T} steps x {w.M} metrics fp32",
+            "kernel": "score_kernel<256,16,11,true,false,false>", "avg_launch_ms": avg,
+            "algorithmic_bytes": alg, "bytes_per_sample": alg / w.samples,
+            "achieved_GB/s": alg / (avg * 1e-3) / 1e9, "frac": alg / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "samples_per_s": w.samples / (avg * 1e-3)}
+
+
 def ledger_leg(torch, det, w, out, stream) -> dict:
     """The bookkeeping beyond the default rule on the same resident scoring outputs
     (persistence per indicator, windowed score sums and their ranking, recurrence):
@@ -190,7 +230,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--cpu-sample-steps", type=int, default=256)
+    ap.add_argument("--cpu-sample-steps", type=int, default=1024)
     ap.add_argument("--stream-steps", type=int, default=100000)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-stream", action="store_true", help="skip the streaming-latency leg")
@@ -271,7 +311,9 @@ def main() -> int:
                      "avg_launch_ms": score_ms,
                      "read_only_ceiling": {"GB/s": x.numel() * 4 / (read_ms * 1e-3) / 1e9, "ms": read_ms,
                                            "what": "the same loads with no arithmetic (gd_probe_read)"},
-                     "issue_view": issue_view(w.samples, score_ms)},
+                     "limited_by": "vector-instruction issue and the barrier-separated phases of the selection, "
+                                   "not HBM: counter traffic equals the algorithmic bytes (see issue_view)",
+                     "issue_view": issue_view(torch, w.samples, score_ms)},
     }
     res["detection"] = detection_report(torch, det, w, x, out, fl)
     if not a.only_batch:
@@ -281,6 +323,9 @@ def main() -> int:
         res["cpu_baseline"] = cpu_baseline(w, x, a.cpu_sample_steps)
     del x, out
     torch.cuda.empty_cache()
+    if not a.only_batch:
+        res["c2"] = c2_leg(torch, stream)
+        torch.cuda.empty_cache()
     if not a.no_stream and not a.only_batch:
         res["streaming"] = streaming_latency(torch, a.stream_steps)
     det.close()

@@ -62,7 +62,6 @@ struct Shared {
     uint32_t dhi[64];
     uint32_t pref[NB + 4];     // exclusive prefix sums of hist (pref[NB] = total), for the MAD shortcut
     uint32_t cand[CAND_CAP + 4];   // 16-byte aligned; read four at a time when ranking
-    uint32_t cand2[CAND_CAP + 4];  // hinted MAD: the candidates kept after the exact test
     uint32_t wpart[16];
     uint32_t below, ncand;
     uint32_t nkept;            // hinted MAD: candidates kept after the exact test
@@ -821,7 +820,9 @@ __device__ __forceinline__ HintedResult hinted_select(SH& sh, const float (&v)[R
     __syncthreads();
     const uint32_t g = rfl(sh.ncand);
     // classify the gathered values exactly (at most CAND_CAP of them); those kept go to a
-    // second list
+    // second list, which takes the place of the prefix sums (read for the last time above)
+    static_assert(NB + 4 >= CAND_CAP + 4, "the prefix array holds the second list");
+    uint32_t* const kept_list = sh.pref;
     if (g <= (uint32_t)CAND_CAP) {
         uint32_t nlt = 0;
 #pragma unroll
@@ -834,7 +835,7 @@ __device__ __forceinline__ HintedResult hinted_select(SH& sh, const float (&v)[R
                 const float d = fabsf(__uint_as_float(x) - med);
                 if (in_l || in_r) {
                     if (d < DI) nlt += 1u;
-                    else if (d <= DO) sh.cand2[atomicAdd(&sh.nkept, 1u)] = __float_as_uint(d);
+                    else if (d <= DO) kept_list[atomicAdd(&sh.nkept, 1u)] = __float_as_uint(d);
                 }
             }
         }
@@ -843,7 +844,7 @@ __device__ __forceinline__ HintedResult hinted_select(SH& sh, const float (&v)[R
     __syncthreads();
     const uint32_t c_in = n_in + rfl(sh.below), kept = rfl(sh.nkept);
     const bool ok = g <= (uint32_t)CAND_CAP && c_in <= k0 && k1 < c_in + kept;
-    if (ok) rank_candidates<NT>(sh, tid, kept, k0 - c_in, k1 - c_in, sh.cand2);
+    if (ok) rank_candidates<NT>(sh, tid, kept, k0 - c_in, k1 - c_in, kept_list);
     else __syncthreads();
     if (tid == 0) {          // (a zero made here: kept in registers for the whole kernel it ends up spilled)
         const uint32_t zero = opaque_v(0u);
@@ -1627,6 +1628,7 @@ hipError_t pick_tiling(const gd_score_args& a, hipStream_t s) {
     // (the 256-thread tilings take 2048 buckets: four workgroups then share a CU's LDS, and
     // their barrier-bound phases overlap)
     if (R <= 4096) return launch<256, 4, 11>(a, s);
+    static_assert(4 * lds_bytes<256, 16, 11>() <= 160 * 1024, "four workgroups of the 16 384-rank tiling share a CU's LDS");
     if (R <= 16384) return launch<256, 16, 11, 1024, 4, 12>(a, s);
     if (R <= 32768) return launch<512, 16, 12, 1024, 8, 12>(a, s);
     if (R <= 65536) return launch<1024, 16, 12>(a, s);
