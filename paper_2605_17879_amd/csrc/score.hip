@@ -65,6 +65,7 @@ struct Shared {
     uint32_t wpart[16];
     uint32_t below, ncand;
     uint32_t nkept;            // hinted MAD: candidates kept after the exact test
+    uint32_t wcnt[16];         // hinted MAD: values gathered by each wave
     uint32_t mres[2][4];       // hinted MAD: edge indices found by the search and a found flag (two slots, used in turn)
     uint32_t smin, smax;       // extremes of the sample keys
     uint32_t d1, d2;           // MAD shortcut: distance interval holding the wanted ranks
@@ -795,41 +796,53 @@ __device__ __forceinline__ HintedResult hinted_select(SH& sh, const float (&v)[R
     const float Da = fminf(dLi, dRi), Db = fmaxf(dLo, dRo);
     const uint32_t n_in = rfl(sh.pref[Rb0] - sh.pref[Lb1 + 1u]);
     if (!(Da > 0.0f) || !(DO >= DI)) return out;
-    // ---- pass 3: gather the values whose distance from the median lies in [Da, Db]
+    // ---- pass 3: gather the values whose distance from the median lies in [Da, Db].  No
+    // round trips: each wave appends to a list of its own inside sh.cand (free at this point),
+    // at a position made of a count kept in a scalar register and the lanes' ballot.
+    constexpr uint32_t NWAVES = NT / WAVE, SUB = (uint32_t)CAND_CAP / NWAVES;
     {
         const float tokm = __uint_as_float(opaque_s(__float_as_uint(med)));
         const float toka = __uint_as_float(opaque_s(__float_as_uint(Da)));
         const uint32_t wspan = __float_as_uint(Db - Da);
+        uint32_t* const mine = sh.cand + w * SUB;
+        uint32_t n = 0;                            // (wave-uniform)
 #pragma unroll
         for (int j = 0; j < ROWS; ++j) {
             uint32_t off[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) off[i] = __float_as_uint(fabsf(v[j][i] - tokm) - toka);   // negative: a large pattern
-            if (min(min(off[0], off[1]), min(off[2], off[3])) <= wspan) {
+            // one test per register row (hits are rare): the smallest offset decides
+            if (__builtin_expect(__ballot(min(min(off[0], off[1]), min(off[2], off[3])) <= wspan) != 0ull, 0)) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    if (off[i] <= wspan) {
-                        uint32_t pos = atomicAdd(&sh.ncand, 1u);
-                        if (pos < (uint32_t)CAND_CAP) sh.cand[pos] = __float_as_uint(v[j][i]);
+                    const bool hit = off[i] <= wspan;
+                    const uint64_t hm = __ballot(hit);
+                    if (hm != 0ull) {
+                        const uint32_t pos = n + __builtin_amdgcn_mbcnt_hi((uint32_t)(hm >> 32),
+                                                                           __builtin_amdgcn_mbcnt_lo((uint32_t)hm, 0u));
+                        if (hit && pos < SUB) mine[pos] = __float_as_uint(v[j][i]);
+                        n += (uint32_t)__popcll(hm);
                     }
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+        if (lane == 0) sh.wcnt[w] = n;
     }
     __syncthreads();
-    const uint32_t g = rfl(sh.ncand);
-    // classify the gathered values exactly (at most CAND_CAP of them); those kept go to a
-    // second list, which takes the place of the prefix sums (read for the last time above)
+    // classify the gathered values exactly; those kept go to a second list, which takes the
+    // place of the prefix sums (read for the last time above).  A wave whose list overflowed
+    // fails the selection for everybody.
     static_assert(NB + 4 >= CAND_CAP + 4, "the prefix array holds the second list");
     uint32_t* const kept_list = sh.pref;
-    if (g <= (uint32_t)CAND_CAP) {
+    const bool fits = __ballot(lane < NWAVES && sh.wcnt[lane < NWAVES ? lane : 0u] > SUB) == 0ull;
+    if (fits) {
         uint32_t nlt = 0;
 #pragma unroll
         for (int q = 0; q < (CAND_CAP + NT - 1) / NT; ++q) {
-            const uint32_t j = tid + q * NT;
-            if (j < g) {
-                const uint32_t x = sh.cand[j];
+            const uint32_t slot = tid + q * NT;
+            if (slot < (uint32_t)CAND_CAP && slot % SUB < sh.wcnt[slot / SUB]) {
+                const uint32_t x = sh.cand[slot];
                 const uint32_t b = (x - lo) >> shift;          // (values outside the bracket: b is huge)
                 const bool in_l = x >= lo && b >= Lb0 && b <= Lb1, in_r = x >= lo && b >= Rb0 && b <= Rb1;
                 const float d = fabsf(__uint_as_float(x) - med);
@@ -843,12 +856,12 @@ __device__ __forceinline__ HintedResult hinted_select(SH& sh, const float (&v)[R
     }
     __syncthreads();
     const uint32_t c_in = n_in + rfl(sh.below), kept = rfl(sh.nkept);
-    const bool ok = g <= (uint32_t)CAND_CAP && c_in <= k0 && k1 < c_in + kept;
+    const bool ok = fits && c_in <= k0 && k1 < c_in + kept;
     if (ok) rank_candidates<NT>(sh, tid, kept, k0 - c_in, k1 - c_in, kept_list);
     else __syncthreads();
     if (tid == 0) {          // (a zero made here: kept in registers for the whole kernel it ends up spilled)
         const uint32_t zero = opaque_v(0u);
-        sh.ncand = zero; sh.nkept = zero; sh.below = zero;
+        sh.nkept = zero; sh.below = zero;
     }
     if (!ok) return out;
     out.q0 = rfl(sh.res[4]);
