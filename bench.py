@@ -175,13 +175,15 @@ def z_variant(torch, det, w, x, stream, alg_bytes: int) -> dict:
             "GB/s": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
 
-def c2_leg(torch, stream) -> dict:
+def c2_leg(torch, stream, host_input: bool = False) -> dict:
     """The 16 384-rank configuration (16 384 ranks x 10 000 steps x 4 metrics, another register
     tiling of the same kernel) in one gd_score_batch call: launch time by HIP events on the
     launch stream, algorithmic bytes, fraction of the HBM peak.  Not part of `value`."""
     from workloads import generate, workload
     w = workload(2)
-    x = generate(w, seed=2, device="cuda")
+    # (the same bytes either way; made on the host and uploaded when a counter profiler is
+    # attached, which does not survive this recipe's device-side generation)
+    x = generate(w, seed=2, device="cpu").cuda() if host_input else generate(w, seed=2, device="cuda")
     det = make_detector(w)
     out = det.alloc_outputs(w.T)
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(7)]
@@ -236,6 +238,10 @@ def main() -> int:
     ap.add_argument("--no-stream", action="store_true", help="skip the streaming-latency leg")
     ap.add_argument("--only-batch", action="store_true",
                     help="only the timed batch steps and the read probe (for profiler runs): no CPU, streaming, z or ledger legs")
+    ap.add_argument("--with-c2", action="store_true",
+                    help="with --only-batch: run the 16 384-rank leg as well (for profiler runs)")
+    ap.add_argument("--c2-host-input", action="store_true",
+                    help="make the 16 384-rank leg's input on the host and upload it (for counter-profiler runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 2 GiB elementwise copy kernel (known traffic) for counter calibration")
     a = ap.parse_args()
@@ -323,8 +329,8 @@ def main() -> int:
         res["cpu_baseline"] = cpu_baseline(w, x, a.cpu_sample_steps)
     del x, out
     torch.cuda.empty_cache()
-    if not a.only_batch:
-        res["c2"] = c2_leg(torch, stream)
+    if not a.only_batch or a.with_c2:
+        res["c2"] = c2_leg(torch, stream, a.c2_host_input)
         torch.cuda.empty_cache()
     if not a.no_stream and not a.only_batch:
         res["streaming"] = streaming_latency(torch, a.stream_steps)
