@@ -672,17 +672,20 @@ __device__ __forceinline__ HintedResult hinted_select(SH& sh, const float (&v)[R
     const uint32_t span0 = hint_hi - hint_lo;
     const int shift = shift_for<LOG_NB>(span0);
     // the bracket is widened to all NB buckets (less than twice the hint's span; the caller
-    // has checked that this stays below KEY_LIMIT)
+    // has checked that this stays below KEY_LIMIT) and starts on a bucket boundary
     constexpr uint32_t bmax = (uint32_t)NB - 1u;
-    const uint32_t lo = hint_lo;
+    const uint32_t lo = hint_lo & ~((1u << shift) - 1u);
     const uint32_t hi = lo + ((uint32_t)NB << shift) - 1u;
     uint32_t* const cnt = sh.dlo;                  // 64 + NB + 64 counters
-    // ---- pass 1: count
+    // ---- pass 1: count.  lo is a multiple of 2^shift, so a key's bucket is its own bits
+    // shifted down, less lo's: the clamp works on the shifted bits and the subtraction
+    // moves into the counter's address (three vector instructions per value).
     {
         const uint32_t tid = opaque_v(threadIdx.x), lane = tid & (WAVE - 1);
-        const uint32_t base = opaque_s(lo - (64u << shift));     // key of counter 0 (mod 2^32)
-        const int cl = 63 - (int)lane, ch = 64 + NB + (int)lane;
-        const int sh_s = (int)opaque_s((uint32_t)shift);
+        const int ql = (int)(lo >> shift);                       // (below 2^30: shift < 2 gives the result up anyway)
+        const int cl = ql - 1 - (int)lane, ch = ql + NB + (int)lane;
+        const uint32_t kb = opaque_s((uint32_t)(64 - ql) * 4u);  // counter 64 is bucket 0 (bytes, mod 2^32)
+        const uint32_t sh_s = opaque_s((uint32_t)shift);
         uint32_t um = 0;
 #pragma unroll
         for (int j = 0; j < ROWS; ++j) {
@@ -690,10 +693,11 @@ __device__ __forceinline__ HintedResult hinted_select(SH& sh, const float (&v)[R
             asm volatile("" : "+v"(row[0]), "+v"(row[1]), "+v"(row[2]), "+v"(row[3]));
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int b = (int)(__float_as_uint(row[i]) - base) >> sh_s;
-                int c;          // b clamped to [cl, ch] (cl < ch): the median of the three
-                asm("v_med3_i32 %0, %1, %2, %3" : "=v"(c) : "v"(b), "v"(cl), "v"(ch));
-                atomicAdd(&cnt[c], 1u);
+                const int q = (int)(__float_as_uint(row[i]) >> sh_s);
+                int c;          // q clamped to [cl, ch] (cl < ch): the median of the three
+                asm("v_med3_i32 %0, %1, %2, %3" : "=v"(c) : "v"(q), "v"(cl), "v"(ch));
+                // counter c - ql + 64, in [63 - lane, 64 + NB + lane]
+                atomicAdd(reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(cnt) + (((uint32_t)c << 2) + kb)), 1u);
             }
             um = max(max(um, __float_as_uint(row[0])), __float_as_uint(row[1]));
             um = max(max(um, __float_as_uint(row[2])), __float_as_uint(row[3]));
@@ -868,6 +872,70 @@ __device__ __forceinline__ HintedResult hinted_select(SH& sh, const float (&v)[R
     out.q1 = rfl(sh.res[5]);
     out.found = 2;
     return out;
+}
+
+// Hints for a column that has no predecessor to take them from (the first step of a
+// workgroup's run): median and quartiles of a sample -- the four values of register row 0
+// of every thread, which cover the whole rank range -- read off a histogram over the
+// sample's own range.  Half the interquartile distance stands in for the MAD (equal to it
+// for a symmetric spread).  Like all hints they are only trusted as far as the counting
+// pass of the hinted selection confirms them, so raw bit patterns serve as keys whatever
+// the column holds.  Thread 0 writes the hints of metric m; ends with a barrier, the work
+// area at rest.
+template <int NT, int LOG_NB, typename SH>
+__device__ __forceinline__ void sample_hints(SH& sh, const float (&row)[4], uint32_t m) {
+    constexpr int BPT = (1 << LOG_NB) / NT;
+    constexpr uint32_t n = 4u * NT;
+    const uint32_t tid = opaque_v(threadIdx.x), lane = tid & (WAVE - 1);
+    uint32_t k[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) k[i] = __float_as_uint(row[i]);
+    const uint32_t mn = wave_min_to_last(min(min(k[0], k[1]), min(k[2], k[3])));
+    const uint32_t mx = wave_max_to_last(max(max(k[0], k[1]), max(k[2], k[3])));
+    if (lane == WAVE - 1) { atomicMin(&sh.smin, mn); atomicMax(&sh.smax, mx); }
+    __syncthreads();
+    const uint32_t smin = rfl(sh.smin), smax = rfl(sh.smax);
+    const int sshift = shift_for<LOG_NB>(smax - smin);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) atomicAdd(&sh.hist[(k[i] - smin) >> sshift], 1u);
+    __syncthreads();
+    if (tid == 0) { sh.smin = 0xFFFFFFFFu; sh.smax = 0; }
+    uint32_t loc[BPT], sum = 0;
+#pragma unroll
+    for (int q = 0; q < BPT; ++q) { loc[q] = sh.hist[tid * BPT + q]; sum += loc[q]; }
+#pragma unroll
+    for (int q = 0; q < BPT; ++q) sh.hist[tid * BPT + q] = 0;
+    uint32_t total;
+    const uint32_t excl = block_excl_scan<NT>(sum, tid, sh.wpart, &total);
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        const uint32_t want = (uint32_t)(r + 1) * (n / 4) - excl;      // sample ranks n/4, n/2, 3n/4
+        if (want < sum) {
+            uint32_t p = 0;
+            bool done = false;
+#pragma unroll
+            for (int q = 0; q < BPT; ++q) {
+                if (!done && want - p < loc[q]) { sh.res[r] = tid * BPT + q; done = true; }
+                p += loc[q];
+            }
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const uint32_t half = (1u << sshift) >> 1;
+        const float q25 = __uint_as_float(smin + (sh.res[0] << sshift) + half);
+        const float q50 = __uint_as_float(smin + (sh.res[1] << sshift) + half);
+        const float q75 = __uint_as_float(smin + (sh.res[2] << sshift) + half);
+        const float hd = 0.5f * (q75 - q25);
+        if (q50 > 0.0f && hd > 0.0f && q50 < 3.0e38f && hd < 3.0e38f) {      // (false for NaNs)
+            sh.hmed[m] = q50;
+            sh.hwl[m] = 1.25f * hd;          // (the reach a run keeps from step to step)
+            sh.hwh[m] = 1.25f * hd;
+            sh.hmad[m] = hd;
+            sh.hok[m] = 1;
+        }
+    }
+    __syncthreads();
 }
 
 // Signed score and node score of one register row, dividing with the IEEE
@@ -1096,6 +1164,12 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         // step to the next: the previous step's median of this metric, with the
         // reach its histogram had, brackets this step's counting pass without
         // sampling.  A bracket that misses is noticed and replaced by the sample's.
+        // (the first step of a run has no predecessor: a sample of the column stands in)
+        bool boot = false;
+        if (FULL && t == t_begin && rfl(sh.hok[m]) == 0) {
+            sample_hints<NT, LOG_NB>(sh, v[0], m);
+            boot = true;
+        }
         bool hinted = rfl(sh.hok[m]) != 0;
         uint32_t hint_lo = 0, hint_hi = 0;
         if (hinted) {
@@ -1122,8 +1196,9 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
             hsel = hr.found;
             umax = hr.umax;
             if (hsel == 0) {
-                hinted = false;                 // (and this metric goes the general way from now on)
-                if (tid == 0) sh.hfast[m] = 0;
+                hinted = false;                 // (and this metric goes the general way from now on,
+                                                // unless the hint was only a sample's)
+                if (tid == 0 && !boot) sh.hfast[m] = 0;
             } else {
                 med = 0.5f * (__uint_as_float(hr.m0) + __uint_as_float(hr.m1));
                 have_mad = hsel == 2;
@@ -1233,6 +1308,8 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
             a.med[t * M + m] = med;
             a.mad[t * M + m] = mad;
             if (hsel) sh.hmad[m] = mad;         // the hinted selection follows median and MAD step by step
+            // (from here on the reach is the exact MAD's, as after the general route)
+            if (boot && hsel == 2) { sh.hwl[m] = 1.25f * mad; sh.hwh[m] = 1.25f * mad; }
         }
         float s = 1.4826f * mad;
         s = fmaxf(s, a.rel_floor * fabsf(med));
