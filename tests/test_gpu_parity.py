@@ -910,3 +910,65 @@ def test_hinted_selection_on_stationary_runs_of_awkward_columns(kind, R):
         gpu_harness.STREAMING_STEPS = None
     say("  report", rep)
     assert rep["z_bit_exact"]
+
+
+# (threads, float4 rows) of the exact-fit tiling of a rank count: the sample behind a run's
+# first hints is register row 0, i.e. ranks (w % rows) * threads * 4 + thread * 4 + 0..3 of
+# thread (w * 64 + lane)
+_SAMPLE_TILING = {1024: (64, 4), 4096: (256, 4), 16384: (256, 16), 65536: (1024, 16)}
+SAMPLE_KINDS = ["far_above", "other_scale", "too_tight", "missing", "negative", "constant", "lowest_values"]
+
+
+@pytest.mark.parametrize("R", sorted(_SAMPLE_TILING))
+@pytest.mark.parametrize("kind", SAMPLE_KINDS)
+def test_first_step_hints_from_unrepresentative_samples(kind, R):
+    """The first step of a run takes its hints from a sample of the column (one register row
+    per thread).  Here exactly the sampled ranks are made misleading -- far above the rest, on
+    another scale, squeezed around the centre, missing, negative, constant, or the lowest
+    values of the column -- so that the sampled median, quartiles or both point the wrong way;
+    the selection must notice and still return the exact statistics.  Every step of these short
+    batches is a first step."""
+    nt, rows = _SAMPLE_TILING[R]
+    T, M = 5, 3
+    say(f"case sampled hints kind={kind} R={R}")
+    g = torch.Generator().manual_seed(len(kind) * 77 + R)
+    n = torch.randn((T, M, R), generator=g, dtype=torch.float64)
+    x = torch.exp(0.02 * n)
+    x[:, 1] = 400.0 / x[:, 1]
+    thread = torch.arange(nt)
+    first = ((thread // 64) % rows) * nt * 4 + thread * 4
+    sampled = (first[:, None] + torch.arange(4)[None, :]).reshape(-1)
+    assert int(sampled.max()) < R and len(set(sampled.tolist())) == 4 * nt
+    s = x[:, :, sampled]
+    if kind == "far_above":
+        s = s * 50.0
+    elif kind == "other_scale":
+        s = 1.0 + (s - 1.0) * 300.0
+        s[:, 1] = 400.0 + (x[:, 1][:, sampled] - 400.0) * 300.0
+        s = s.abs() + 1e-3
+    elif kind == "too_tight":
+        c = x.median(dim=-1, keepdim=True).values
+        s = c + (s - c) * 1e-3
+    elif kind == "missing":
+        s = torch.full_like(s, float("nan"))
+        s[:, 2] = x[:, 2][:, sampled]                       # (one metric keeps its samples)
+    elif kind == "negative":
+        s = -s
+    elif kind == "constant":
+        s = torch.full_like(s, 1.0)
+    elif kind == "lowest_values":
+        srt = torch.sort(x, dim=-1).values                  # the sample holds the lowest values,
+        rest = torch.ones(R, dtype=torch.bool)              # the other ranks the rest in order
+        rest[sampled] = False
+        x[:, :, rest] = srt[:, :, 4 * nt:]
+        s = srt[:, :, : 4 * nt]
+    x[:, :, sampled] = s
+    x = x.to(torch.float32)
+    p = oracle_params(R=R, M=M, W=4, k=2, directions=(1, -1, 0))
+    import gpu_harness
+    gpu_harness.STREAMING_STEPS = 0                             # whole-run route
+    try:
+        rep = run_and_compare(p, x, topk_k=min(8, R // 8), chunks=[T], label=f"sample-{kind}-R{R}")
+    finally:
+        gpu_harness.STREAMING_STEPS = None
+    say("  report", rep)
