@@ -76,7 +76,7 @@ struct Shared {
     float hmed[8], hwl[8], hwh[8], hmad[8];
     uint32_t hok[8];
     uint32_t hfast[8];         // the hinted selection below has not failed for this metric yet
-    uint8_t nodeb[MAX_NODES];
+    alignas(8) uint8_t nodeb[MAX_NODES];        // the step's node mask bytes, read eight at a time
     uint64_t ranka[MAX_NODES / 8 > 0 ? MAX_NODES / 8 : 1];     // the step's rank anomaly words (zero between steps)
 };
 
@@ -1497,28 +1497,29 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
     // into the step's bit words in LDS (all zero between steps) only by the waves that
     // hold one, and the finished words are copied out below.
     const uint32_t min_signals = rfl(a.min_signals), others_mask = ~(0x01010101u << a.primary);
+    // multi-signal rule on four mask bytes at once: primary bit set and at least min_signals
+    // bits in the byte; the answer is bit 0 of each byte
+    auto rule4 = [&](uint32_t E) -> uint32_t {
+        const uint32_t prim_set = (E >> a.primary) & 0x01010101u;
+        if (min_signals <= 2u) {
+            // (two signals: the primary's and any other -- bit 7 of "low seven bits + 0x7F",
+            // or bit 7 itself, says that a byte is not zero)
+            const uint32_t others = E & others_mask;
+            const uint32_t some = (((others & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | others) >> 7;
+            return min_signals <= 1u ? prim_set : (prim_set & some);
+        }
+        // per-byte popcount >= min_signals (adding 0x80 - min_signals carries into bit 7)
+        uint32_t pc = E - ((E >> 1) & 0x55555555u);
+        pc = (pc & 0x33333333u) + ((pc >> 2) & 0x33333333u);
+        pc = (pc + (pc >> 4)) & 0x0F0F0F0Fu;
+        return prim_set & ((pc + (0x80u - min_signals) * 0x01010101u) >> 7);
+    };
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
         const bool valid = FULL || rbase(j, to) < R;
         const uint32_t Ej = emask[j * NT + to / 4];
         if (valid) *reinterpret_cast<uint32_t*>(erow + rbase(j, to)) = Ej;
-        // multi-signal rule on the four mask bytes at once: primary bit set and at least
-        // min_signals bits in the byte
-        const uint32_t prim_set = (Ej >> a.primary) & 0x01010101u;
-        uint32_t an;
-        if (min_signals <= 2u) {
-            // (two signals: the primary's and any other -- bit 7 of "low seven bits + 0x7F",
-            // or bit 7 itself, says that a byte is not zero)
-            const uint32_t others = Ej & others_mask;
-            const uint32_t some = (((others & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | others) >> 7;
-            an = min_signals <= 1u ? prim_set : (prim_set & some);
-        } else {
-            // per-byte popcount >= min_signals (adding 0x80 - min_signals carries into bit 7)
-            uint32_t pc = Ej - ((Ej >> 1) & 0x55555555u);
-            pc = (pc & 0x33333333u) + ((pc >> 2) & 0x33333333u);
-            pc = (pc + (pc >> 4)) & 0x0F0F0F0Fu;
-            an = prim_set & ((pc + (0x80u - min_signals) * 0x01010101u) >> 7);
-        }
+        uint32_t an = rule4(Ej);
         if (!valid) an = 0u;
         if (__builtin_expect(__ballot(an != 0u) != 0ull, 0)) {
             // the lane's four ranks are bits rbase % 32 .. + 3 of 32-bit word rbase / 32
@@ -1533,24 +1534,48 @@ __global__ __launch_bounds__(NT, 4) void score_kernel(const gd_score_args a) {  
         a.rank_anom[t * RW + q] = sh.ranka[q];
         sh.ranka[q] = 0;
     }
-    if (FULL) {                                 // N == NT * ROWS / 2: a fixed number of rounds
+    if (FULL && ROWS == 16) {
+        // N == 8 * NT: eight nodes per thread -- one 8-byte read of the staged bytes and one
+        // 8-byte store; the rule byte-parallel as for the ranks; eight consecutive lanes make
+        // one 64-bit anomaly word
+        const uint32_t tq = opaque_v((uint32_t)tid), sl = tq & 7u;
+        const uint2 nb = *reinterpret_cast<const uint2*>(&sh.nodeb[8 * tq]);
+        uint8_t* nm = a.node_mask + t * N + 8 * tq;
+        if (((uintptr_t)a.node_mask & 7u) == 0) {
+            *reinterpret_cast<uint2*>(nm) = nb;
+        } else {
 #pragma unroll
-        for (int q = 0; q < (ROWS + 1) / 2; ++q) {
-            const uint32_t n = opaque_v((uint32_t)tid) + (uint32_t)q * NT;
-            if (ROWS % 2 == 0 || n < N) a.node_mask[t * N + n] = sh.nodeb[n];
+            for (int i = 0; i < 8; ++i) nm[i] = (uint8_t)((i < 4 ? nb.x : nb.y) >> (8 * (i & 3)));
         }
+        const uint32_t a0 = rule4(nb.x), a1 = rule4(nb.y);
+        const uint32_t ab = ((a0 | (a0 >> 7) | (a0 >> 14) | (a0 >> 21)) & 0xFu) |
+                            (((a1 | (a1 >> 7) | (a1 >> 14) | (a1 >> 21)) & 0xFu) << 4);
+        uint32_t wlo = sl < 4u ? ab << (8u * sl) : 0u;
+        uint32_t whi = sl >= 4u ? ab << (8u * (sl - 4u)) : 0u;
+        wlo |= lane_xor<1>(wlo); whi |= lane_xor<1>(whi);
+        wlo |= lane_xor<2>(wlo); whi |= lane_xor<2>(whi);
+        wlo |= lane_xor<4>(wlo); whi |= lane_xor<4>(whi);
+        if (sl == 0u) a.node_anom[t * NWD + tq / 8u] = ((uint64_t)whi << 32) | wlo;
     } else {
-        for (uint32_t n = tid; n < N; n += NT) a.node_mask[t * N + n] = sh.nodeb[n];
-    }
-    for (uint32_t wd = w; wd < NWD; wd += NWAVES) {
-        const uint32_t n = wd * 64 + lane;
-        bool an = false;
-        if (n < N) {
-            const uint32_t b = sh.nodeb[n];
-            an = ((b >> a.primary) & 1u) && (uint32_t)__popc(b) >= a.min_signals;
+        if (FULL) {                             // N == NT * ROWS / 2: a fixed number of rounds
+#pragma unroll
+            for (int q = 0; q < (ROWS + 1) / 2; ++q) {
+                const uint32_t n = opaque_v((uint32_t)tid) + (uint32_t)q * NT;
+                if (ROWS % 2 == 0 || n < N) a.node_mask[t * N + n] = sh.nodeb[n];
+            }
+        } else {
+            for (uint32_t n = tid; n < N; n += NT) a.node_mask[t * N + n] = sh.nodeb[n];
         }
-        const uint64_t word = __ballot(an);
-        if (lane == 0) a.node_anom[t * NWD + wd] = word;
+        for (uint32_t wd = w; wd < NWD; wd += NWAVES) {
+            const uint32_t n = wd * 64 + lane;
+            bool an = false;
+            if (n < N) {
+                const uint32_t b = sh.nodeb[n];
+                an = ((b >> a.primary) & 1u) && (uint32_t)__popc(b) >= a.min_signals;
+            }
+            const uint64_t word = __ballot(an);
+            if (lane == 0) a.node_anom[t * NWD + wd] = word;
+        }
     }
     }   // steps of this workgroup
 }
