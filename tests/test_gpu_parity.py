@@ -972,3 +972,35 @@ def test_first_step_hints_from_unrepresentative_samples(kind, R):
     finally:
         gpu_harness.STREAMING_STEPS = None
     say("  report", rep)
+
+
+@pytest.mark.parametrize("R", [16384, 65536])
+def test_node_mask_at_any_byte_offset(R):
+    """The node mask is a byte array and may start at any address: the batch route writes it
+    eight bytes at a time where the address allows and byte by byte otherwise.  Both ways
+    must give the oracle's bytes (and leave the bytes around the array alone)."""
+    T, M = 3, 2
+    say(f"case node mask offsets R={R}")
+    g = torch.Generator().manual_seed(R + 5)
+    x = torch.exp(0.02 * torch.randn((T, M, R), generator=g, dtype=torch.float64))
+    x[:, :, 64:72] *= 1.3                                    # a slow node: some node bits are set
+    x[:, :, 4096:4104] *= 1.2
+    x = x.to(torch.float32)
+    p = oracle_params(R=R, M=M, W=4, k=2, directions=(1, 1))
+    want = oracle.score(p, x.numpy(), want_z=False)
+    assert want.node_mask.any()
+    det = detector_for(p)
+    det.set_streaming_steps(0)                              # the batch route
+    xd = x.cuda()
+    N = R // 8
+    for off in (0, 1, 4, 7):
+        out = det.alloc_outputs(T)
+        big = torch.full((T * N + 32,), 0xAB, dtype=torch.uint8, device="cuda")
+        out["node_mask"] = big[8 + off: 8 + off + T * N].view(T, N)
+        assert out["node_mask"].data_ptr() % 8 == off
+        det.score_batch(xd, out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out["node_mask"].cpu().numpy(), want.node_mask), f"offset {off}"
+        assert np.array_equal(out["node_anom"].cpu().numpy().view(np.uint64), want.node_anom), f"offset {off}"
+        assert bool((big[: 8 + off] == 0xAB).all()) and bool((big[8 + off + T * N:] == 0xAB).all())
+    det.close()
